@@ -1,0 +1,152 @@
+/*
+ * leanquant.h -- C ABI of the MI355X (gfx950) LeanQuant per-layer quantization pass.
+ *
+ * The four compute calls are the four parts of Algorithm 1 of the paper
+ * (arXiv 2407.10032, "LeanQuant for LLM quantization"):
+ *
+ *   lq_hessian_accumulate   line 3        H <- 2 X X^T
+ *   lq_cholesky_inv         line 4        H^-1 <- Cholesky([H + df avg(diag H) I]^-1)
+ *   lq_fit_grid             lines 5-9     loss-error-aware grid per output channel
+ *                                         (Eq. 5 with Eq. 6 init, or Eq. 7 with Eq. 8)
+ *   lq_quantize_layer       lines 10-21   blocked quantize-and-propagate column loop
+ *
+ * Conventions shared by all calls
+ *   - Every pointer is a DEVICE pointer unless the comment says "host".  The
+ *     caller owns every buffer; the library allocates no device memory and
+ *     keeps no state between calls apart from a thread-local error string.
+ *   - All matrices are row-major fp32 with an explicit leading dimension
+ *     counted in elements.  W is r x c with rows = output channels and
+ *     columns = input channels, as in the paper (W in R^{r x c}).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; they do not synchronize.  Results are
+ *     bit-identical from run to run (no atomics on floating-point data).
+ *   - `ws` is caller-provided scratch of at least lq_workspace_bytes() bytes,
+ *     256-byte aligned, whose contents are undefined before and after a call.
+ *   - Return value: LQ_OK or an error code; argument errors are found on the
+ *     host before anything is launched.  lq_last_error() gives the text.
+ */
+#ifndef LEANQUANT_H
+#define LEANQUANT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LQ_OK = 0,
+  LQ_ERR_INVALID_ARG = 1, /* null pointer, bad size, bad leading dimension, bad parameter */
+  LQ_ERR_NOT_PD = 2,      /* reserved for synchronous checks; device-side failures use `info` */
+  LQ_ERR_UNSUPPORTED = 3, /* valid request outside what the kernels cover (limits below)   */
+  LQ_ERR_WORKSPACE = 4,   /* ws is NULL, misaligned or smaller than lq_workspace_bytes()    */
+  LQ_ERR_HIP = 5          /* a HIP runtime call or launch failed                            */
+} lq_status;
+
+typedef enum { LQ_GRID_NONUNIFORM = 0, LQ_GRID_AFFINE = 1 } lq_grid_mode;
+
+typedef enum {
+  LQ_CALL_HESSIAN = 0,
+  LQ_CALL_CHOLESKY = 1,
+  LQ_CALL_FIT_GRID = 2,
+  LQ_CALL_QUANTIZE = 3
+} lq_call;
+
+/* Inputs of Algorithm 1 other than W and X, plus the grid-search constants. */
+typedef struct lq_params {
+  int32_t bits;            /* b: 2, 3 or 4                                                  */
+  int32_t mode;            /* lq_grid_mode                                                  */
+  int32_t group_size;      /* affine only: columns per (S, Z) group; 0 = whole row.
+                              Must divide c.  Must be 0 in non-uniform mode (Section 2.1:
+                              one grid per row).                                            */
+  int32_t block;           /* B, lazy-update block width; 128 is the supported value        */
+  float damp;              /* df, dampening factor (Section 2.2: 0.01)                      */
+  float p;                 /* outlier-preservation strength of Eq. 5 / Eq. 7 (paper: 4)     */
+  int32_t T;               /* partitions of the weight range in Eq. 7 (paper: 2048)         */
+  int32_t t_override;      /* < 0: t = floor(0.2T / 0.3T / 0.4T) for b = 4 / 3 / 2 (Eq. 8);
+                              >= 0: use this t (0 = plain min-max grid); at most T/2        */
+  int32_t kmeans_max_iter; /* cap on Lloyd updates (the fit stops earlier at a fixed point) */
+} lq_params;
+
+/* Fill *P with the paper's settings: b = 4, non-uniform, B = 128, df = 0.01, p = 4,
+ * T = 2048, t from Eq. 8, at most 100 Lloyd updates.  P: host pointer. */
+void lq_params_default(lq_params* P);
+
+/*
+ * Algorithm 1 line 3 / Section 2.2: H <- H + 2 X^T X for a chunk of calibration
+ * tokens.  The paper writes X as c x N and H = 2 X X^T; here tokens are rows.
+ *   H    [c x c], leading dimension ldh >= c.  Read and written in full (both
+ *        triangles are kept equal).  The caller zero-fills it before the first chunk.
+ *   X    [n_tokens x c], leading dimension ldx >= c.  Read only.
+ *   n_tokens >= 0 (0 is a no-op), c >= 1.
+ *   ws   LQ_CALL_HESSIAN scratch (partial sums of the token split).
+ * The token range is split over workgroups and the partial sums are added in a
+ * fixed order, so the result does not depend on scheduling.
+ */
+lq_status lq_hessian_accumulate(float* H, int64_t ldh, const float* X, int64_t n_tokens, int64_t c,
+                                int64_t ldx, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Algorithm 1 line 4: dampen, invert, factor.
+ *   H         [c x c] (ldh), symmetric, read only.
+ *   damp      df; lambda = df * mean(diag H) is added to the diagonal.
+ *   U         [c x c] (ldu) out: the UPPER Cholesky factor of (H + lambda I)^-1,
+ *             i.e. (H + lambda I)^-1 = U^T U; entries below the diagonal are set to 0.
+ *             (Rows U[j, j:] are what lines 16-19 of Algorithm 1 read.)
+ *   hinv_diag [c] out: diag((H + lambda I)^-1), the inverse-Hessian diagonal of Eq. 5 / Eq. 7.
+ *   info      one int32 out: 0 on success; k > 0 if the damped matrix is not positive
+ *             definite, where k - 1 is the column at which a non-positive pivot appeared
+ *             (U and hinv_diag are then meaningless but finite work still completes).
+ *   ws        LQ_CALL_CHOLESKY scratch.
+ * Computed as one factorization H_d = R R^T with R upper triangular followed by the
+ * triangular inverse U = R^-1, which equals the literal invert-then-factor result.
+ */
+lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, float damp, float* U, int64_t ldu,
+                          float* hinv_diag, int32_t* info, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Algorithm 1 lines 5-9: learn the grid of every row from the ORIGINAL weights.
+ *   W          [r x c] (ldw), read only.
+ *   hinv_diag  [c], from lq_cholesky_inv; importance omega_i is proportional to hinv_diag_i^-p.
+ *   P          host pointer.
+ *   grid  out  non-uniform: [r x 2^bits] ascending centroids of weighted k-means
+ *                           (Eq. 5) started from the evenly spaced grid (Eq. 6);
+ *              affine:      [r x (c / group) x 2] = (S, Z) minimizing Eq. 7 over
+ *                           t_min, t_max in {0..t}; Z is an integer stored as float.
+ * Limits: non-uniform c <= 16384; affine group (or row when group_size = 0) <= 8192.
+ */
+lq_status lq_fit_grid(const float* W, int64_t r, int64_t c, int64_t ldw, const float* hinv_diag,
+                      const lq_params* P, float* grid, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Algorithm 1 lines 10-21: for each block of B columns, quantize column by column
+ * against the row's grid, scale the error by U_jj, propagate it inside the block,
+ * then apply the dense rank-B update to all later columns.
+ *   W        [r x c] (ldw) in/out: the working copy; on return it holds W_hat,
+ *            the dequantized result Algorithm 1 returns.
+ *   U        [c x c] (ldu) from lq_cholesky_inv, read only.
+ *   grid     as written by lq_fit_grid for the same P.
+ *   codes    [r x c] uint8 out (leading dimension c): index into the ascending grid
+ *            (non-uniform) or w_int of Section 2.1 (affine).
+ *   row_loss [r] out or NULL: 1/2 sum_j E_kj^2, the loss errors of Eq. 3 summed per row.
+ *   ws       LQ_CALL_QUANTIZE scratch (the r x B error block E).
+ */
+lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t ldw, const float* U, int64_t ldu,
+                            const float* grid, const lq_params* P, uint8_t* codes, float* row_loss,
+                            void* ws, size_t ws_bytes, void* stream);
+
+/* Scratch bytes a call needs (host-only computation).  n_tokens is used by
+ * LQ_CALL_HESSIAN only; r by FIT_GRID/QUANTIZE; P may be NULL for HESSIAN/CHOLESKY. */
+size_t lq_workspace_bytes(int which_call, int64_t r, int64_t c, int64_t n_tokens, const lq_params* P);
+
+/* Text of the last error on the calling thread ("" if none).  Never NULL.  Host pointer. */
+const char* lq_last_error(void);
+
+/* Library version as "major.minor". */
+const char* lq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LEANQUANT_H */

@@ -1,0 +1,172 @@
+"""ctypes binding of libleanquant.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point in
+include/leanquant.h and takes torch CUDA tensors where the C call takes device
+pointers.  Nothing is computed here; PyTorch supplies device memory and the
+current stream.  Importing works without the library (so that the package can be
+built first); the first call fails loudly if libleanquant.so is missing.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libleanquant.so")
+
+LQ_OK, LQ_ERR_INVALID_ARG, LQ_ERR_NOT_PD, LQ_ERR_UNSUPPORTED, LQ_ERR_WORKSPACE, LQ_ERR_HIP = range(6)
+LQ_GRID_NONUNIFORM, LQ_GRID_AFFINE = 0, 1
+LQ_CALL_HESSIAN, LQ_CALL_CHOLESKY, LQ_CALL_FIT_GRID, LQ_CALL_QUANTIZE = range(4)
+
+EXPORTS = ("lq_params_default", "lq_hessian_accumulate", "lq_cholesky_inv", "lq_fit_grid",
+           "lq_quantize_layer", "lq_workspace_bytes", "lq_last_error", "lq_version")
+
+
+class lq_params(ctypes.Structure):
+    _fields_ = [("bits", ctypes.c_int32), ("mode", ctypes.c_int32), ("group_size", ctypes.c_int32),
+                ("block", ctypes.c_int32), ("damp", ctypes.c_float), ("p", ctypes.c_float),
+                ("T", ctypes.c_int32), ("t_override", ctypes.c_int32),
+                ("kmeans_max_iter", ctypes.c_int32)]
+
+
+class LeanQuantError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__("leanquant status %d: %s" % (status, text))
+        self.status = status
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libleanquant.so (built in-tree by paper_2407_10032_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libleanquant.so is not built: run `python -m paper_2407_10032_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, vp, sz, fp = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
+    pp = ctypes.POINTER(lq_params)
+    lib.lq_params_default.argtypes = [pp]
+    lib.lq_params_default.restype = None
+    lib.lq_hessian_accumulate.argtypes = [vp, i64, vp, i64, i64, i64, vp, sz, vp]
+    lib.lq_hessian_accumulate.restype = ctypes.c_int
+    lib.lq_cholesky_inv.argtypes = [vp, i64, i64, fp, vp, i64, vp, vp, vp, sz, vp]
+    lib.lq_cholesky_inv.restype = ctypes.c_int
+    lib.lq_fit_grid.argtypes = [vp, i64, i64, i64, vp, pp, vp, vp, sz, vp]
+    lib.lq_fit_grid.restype = ctypes.c_int
+    lib.lq_quantize_layer.argtypes = [vp, i64, i64, i64, vp, i64, vp, pp, vp, vp, vp, sz, vp]
+    lib.lq_quantize_layer.restype = ctypes.c_int
+    lib.lq_workspace_bytes.argtypes = [ctypes.c_int, i64, i64, i64, pp]
+    lib.lq_workspace_bytes.restype = sz
+    lib.lq_last_error.argtypes = []
+    lib.lq_last_error.restype = ctypes.c_char_p
+    lib.lq_version.argtypes = []
+    lib.lq_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != LQ_OK:
+        raise LeanQuantError(status, load().lq_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor], dtype: torch.dtype, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError("%s must be a CUDA (HIP) tensor" % name)
+    if t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    return t.data_ptr()
+
+
+def _ld(t: torch.Tensor, name: str) -> int:
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError("%s must be a 2-D tensor with unit column stride" % name)
+    return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ws(ws: Optional[torch.Tensor]):
+    if ws is None:
+        return None, 0
+    if not ws.is_cuda or ws.dtype != torch.uint8 or not ws.is_contiguous():
+        raise TypeError("workspace must be a contiguous CUDA uint8 tensor")
+    return ws.data_ptr(), ws.numel()
+
+
+def lq_params_default(**overrides) -> lq_params:
+    P = lq_params()
+    load().lq_params_default(ctypes.byref(P))
+    for k, v in overrides.items():
+        if not hasattr(P, k):
+            raise AttributeError(k)
+        setattr(P, k, v)
+    return P
+
+
+def lq_workspace_bytes(which_call: int, r: int, c: int, n_tokens: int = 0,
+                       P: Optional[lq_params] = None) -> int:
+    return int(load().lq_workspace_bytes(which_call, r, c, n_tokens, ctypes.byref(P) if P is not None else None))
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    """Device scratch for a call (torch's allocator returns >= 256-byte aligned blocks)."""
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def lq_hessian_accumulate(H: torch.Tensor, X: torch.Tensor, ws: torch.Tensor) -> None:
+    """H += 2 X^T X.  H [c x c] fp32, X [n_tokens x c] fp32."""
+    c = H.shape[0]
+    wp, wn = _ws(ws)
+    _check(load().lq_hessian_accumulate(_ptr(H, torch.float32, "H"), _ld(H, "H"),
+                                        _ptr(X, torch.float32, "X"), X.shape[0], c, _ld(X, "X"),
+                                        wp, wn, _stream()))
+
+
+def lq_cholesky_inv(H: torch.Tensor, damp: float, U: torch.Tensor, hinv_diag: torch.Tensor,
+                    info: torch.Tensor, ws: torch.Tensor) -> None:
+    c = H.shape[0]
+    wp, wn = _ws(ws)
+    _check(load().lq_cholesky_inv(_ptr(H, torch.float32, "H"), _ld(H, "H"), c, float(damp),
+                                  _ptr(U, torch.float32, "U"), _ld(U, "U"),
+                                  _ptr(hinv_diag, torch.float32, "hinv_diag"),
+                                  _ptr(info, torch.int32, "info"), wp, wn, _stream()))
+
+
+def lq_fit_grid(W: torch.Tensor, hinv_diag: torch.Tensor, P: lq_params, grid: torch.Tensor,
+                ws: torch.Tensor) -> None:
+    r, c = W.shape
+    wp, wn = _ws(ws)
+    _check(load().lq_fit_grid(_ptr(W, torch.float32, "W"), r, c, _ld(W, "W"),
+                              _ptr(hinv_diag, torch.float32, "hinv_diag"), ctypes.byref(P),
+                              _ptr(grid, torch.float32, "grid"), wp, wn, _stream()))
+
+
+def lq_quantize_layer(W: torch.Tensor, U: torch.Tensor, grid: torch.Tensor, P: lq_params,
+                      codes: torch.Tensor, row_loss: Optional[torch.Tensor], ws: torch.Tensor) -> None:
+    r, c = W.shape
+    wp, wn = _ws(ws)
+    _check(load().lq_quantize_layer(_ptr(W, torch.float32, "W"), r, c, _ld(W, "W"),
+                                    _ptr(U, torch.float32, "U"), _ld(U, "U"),
+                                    _ptr(grid, torch.float32, "grid"), ctypes.byref(P),
+                                    _ptr(codes, torch.uint8, "codes"),
+                                    _ptr(row_loss, torch.float32, "row_loss"), wp, wn, _stream()))
+
+
+def lq_last_error() -> str:
+    return load().lq_last_error().decode()
+
+
+def lq_version() -> str:
+    return load().lq_version().decode()

@@ -1,0 +1,339 @@
+// lq_cholesky_inv: U = upper Cholesky factor of (H + lambda I)^-1 and its diagonal
+// (Algorithm 1 line 4; dampening and Cholesky as described in Section 2.2).
+//
+// Route: with J the index reversal, factor J H_d J = L L^T (ordinary lower Cholesky),
+// so H_d = R R^T with R = J L J upper triangular; then H_d^-1 = R^-T R^-1 and, by
+// uniqueness of the Cholesky factor, U = R^-1 = J L^-1 J.  One blocked factorization
+// and one blocked triangular inverse (2/3 c^3 flop) instead of invert-then-factor.
+// diag(H_d^-1)_i = sum_k U_ki^2 falls out as the column norms of L^-1.
+//
+// All block operations work on a zero/identity padded copy whose order is a multiple
+// of 128, so no tile needs edge handling.  Panel and trailing updates are 128-deep
+// fp32 MFMA tile products; the 128 x 128 diagonal blocks are factored and inverted
+// by one workgroup in LDS.
+#include "lq_common.h"
+#include "lq_mfma.h"
+
+namespace {
+
+using lq::TILE;
+using lq::WG_THREADS;
+constexpr int NB = 128;
+constexpr int DLD = 129;  // LDS leading dimension of the diagonal block
+
+// ---------------------------------------------------------------- small kernels
+__global__ __launch_bounds__(1024) void diag_mean_kernel(const float* __restrict__ H, int64_t ldh,
+                                                         int64_t c, float damp,
+                                                         float* __restrict__ scal,
+                                                         int32_t* __restrict__ info) {
+  __shared__ double red[1024];
+  double s = 0.0;
+  for (int64_t i = threadIdx.x; i < c; i += 1024) s += (double)H[i * ldh + i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = 512; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    scal[0] = (float)((double)damp * red[0] / (double)c);
+    *info = 0;
+  }
+}
+
+// A[i][j] = H_d[c-1-i][c-1-j] for i, j < c; identity on the padding.
+__global__ __launch_bounds__(256) void flip_damp_kernel(const float* __restrict__ H, int64_t ldh,
+                                                        int64_t c, int64_t cp,
+                                                        const float* __restrict__ scal,
+                                                        float* __restrict__ A) {
+  int64_t i = blockIdx.y;
+  int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (j >= cp) return;
+  float v;
+  if (i < c && j < c) {
+    v = H[(c - 1 - i) * ldh + (c - 1 - j)];
+    if (i == j) v += scal[0];
+  } else {
+    v = (i == j) ? 1.0f : 0.0f;
+  }
+  A[i * cp + j] = v;
+}
+
+__global__ __launch_bounds__(256) void fill_kernel(float* __restrict__ p, int64_t n, float v) {
+  int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i + 3 < n) {
+    *reinterpret_cast<float4*>(p + i) = make_float4(v, v, v, v);
+  } else {
+    for (; i < n; ++i) p[i] = v;
+  }
+}
+
+// Factor the diagonal block kb in LDS (column by column), invert the factor, write
+// L_kk back (upper part zeroed) and its inverse to Dinv[kb] (128 x 128, ld 128).
+__global__ __launch_bounds__(256) void potrf_diag_kernel(float* __restrict__ A, int64_t cp, int kb,
+                                                         float* __restrict__ Dinv,
+                                                         int32_t* __restrict__ info, int64_t c) {
+  extern __shared__ __align__(16) float sm[];
+  float* sL = sm;                // [128][129]
+  float* sX = sm + NB * DLD;     // [128][129]
+  const int tid = threadIdx.x;
+  float* tile = A + ((int64_t)kb * NB) * cp + (int64_t)kb * NB;
+  for (int f = tid; f < NB * NB / 4; f += 256) {
+    int row = f >> 5, c4 = f & 31;
+    float4 v = *reinterpret_cast<const float4*>(tile + (int64_t)row * cp + 4 * c4);
+    float* d = sL + row * DLD + 4 * c4;
+    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+  }
+  __syncthreads();
+
+  const int ri = tid & 127, half = tid >> 7;
+  for (int j = 0; j < NB; ++j) {
+    float pv = sL[j * DLD + j];
+    if (!(pv > 0.0f)) {
+      int64_t q = (int64_t)kb * NB + j;
+      if (tid == 0 && q < c && *info == 0) *info = (int32_t)(c - 1 - q) + 1;
+      pv = 1.0f;
+    }
+    const float dj = sqrtf(pv);
+    const float rd = 1.0f / dj;
+    __syncthreads();  // everyone has read the pivot
+    if (half == 0) {
+      if (ri > j) sL[ri * DLD + j] *= rd;
+      else if (ri == j) sL[j * DLD + j] = dj;
+    }
+    __syncthreads();
+    if (ri > j) {
+      const float lij = sL[ri * DLD + j];
+      for (int k = j + 1 + half; k <= ri; k += 2) sL[ri * DLD + k] -= lij * sL[k * DLD + j];
+    }
+    __syncthreads();
+  }
+
+  // X = L^-1, one column per thread (columns are independent).
+  if (tid < NB) {
+    const int j = tid;
+    for (int i = 0; i < j; ++i) sX[i * DLD + j] = 0.0f;
+    sX[j * DLD + j] = 1.0f / sL[j * DLD + j];
+    for (int i = j + 1; i < NB; ++i) {
+      float acc = 0.0f;
+      for (int k = j; k < i; ++k) acc += sL[i * DLD + k] * sX[k * DLD + j];
+      sX[i * DLD + j] = -acc / sL[i * DLD + i];
+    }
+  }
+  __syncthreads();
+
+  float* dinv = Dinv + (int64_t)kb * NB * NB;
+  for (int f = tid; f < NB * NB; f += 256) {
+    int row = f >> 7, col = f & 127;
+    tile[(int64_t)row * cp + col] = (col <= row) ? sL[row * DLD + col] : 0.0f;
+    dinv[f] = sX[row * DLD + col];
+  }
+}
+
+// ---------------------------------------------------------------- 128-deep tile products
+enum ChMode { CH_PANEL = 0, CH_SYRK = 1, CH_TRI_ROW = 2, CH_TRI_UPD = 3 };
+
+struct ChArgs {
+  float* A;      // factor workspace (cp x cp), lower triangle = L
+  float* Xb;     // inverse workspace (cp x cp)
+  float* Dinv;   // inverted diagonal blocks
+  int64_t cp;
+  int step;      // kb (PANEL, SYRK) or i (TRI_ROW, TRI_UPD)
+};
+
+template <int MODE>
+__global__ __launch_bounds__(WG_THREADS, 2) void chol_gemm_kernel(ChArgs a) {
+  __shared__ float sA[TILE * lq::RM_LD];
+  __shared__ float sB[TILE * lq::RM_LD];
+  static_assert(TILE * lq::RM_LD >= lq::RM_KT * TILE, "k-major chunk must fit");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int b = blockIdx.x;
+  const int64_t cp = a.cp;
+
+  const float* Aop; int64_t lda;
+  const float* Bop; int64_t ldb;
+  float* Out; int64_t ldo;
+  constexpr bool B_KMAJOR = (MODE == CH_TRI_ROW || MODE == CH_TRI_UPD);
+  constexpr bool SUBTRACT = (MODE == CH_SYRK || MODE == CH_TRI_UPD);
+
+  if (MODE == CH_PANEL) {
+    int64_t i = a.step + 1 + b;
+    Aop = a.A + (i * NB) * cp + (int64_t)a.step * NB; lda = cp;
+    Bop = a.Dinv + (int64_t)a.step * NB * NB; ldb = NB;
+    Out = a.A + (i * NB) * cp + (int64_t)a.step * NB; ldo = cp;
+  } else if (MODE == CH_SYRK) {
+    int ii = (int)((sqrtf(8.0f * (float)b + 1.0f) - 1.0f) * 0.5f);
+    while (ii * (ii + 1) / 2 > b) --ii;
+    while ((ii + 1) * (ii + 2) / 2 <= b) ++ii;
+    int jj = b - ii * (ii + 1) / 2;
+    int64_t i = a.step + 1 + ii, j = a.step + 1 + jj;
+    Aop = a.A + (i * NB) * cp + (int64_t)a.step * NB; lda = cp;
+    Bop = a.A + (j * NB) * cp + (int64_t)a.step * NB; ldb = cp;
+    Out = a.A + (i * NB) * cp + j * NB; ldo = cp;
+  } else if (MODE == CH_TRI_ROW) {
+    int64_t i = a.step, k = b;
+    Out = a.Xb + (i * NB) * cp + k * NB; ldo = cp;
+    if (k == i) {
+      const float* src = a.Dinv + i * NB * NB;
+      for (int f = tid; f < NB * NB / 4; f += WG_THREADS) {
+        int row = f >> 5, c4 = f & 31;
+        *reinterpret_cast<float4*>(Out + (int64_t)row * ldo + 4 * c4) =
+            *reinterpret_cast<const float4*>(src + row * NB + 4 * c4);
+      }
+      return;
+    }
+    Aop = a.Dinv + i * NB * NB; lda = NB;
+    Bop = Out; ldb = cp;
+  } else {
+    int64_t i = a.step;
+    int jj = b / (int)(i + 1), k = b - jj * (int)(i + 1);
+    int64_t j = i + 1 + jj;
+    Aop = a.A + (j * NB) * cp + i * NB; lda = cp;
+    Bop = a.Xb + (i * NB) * cp + (int64_t)k * NB; ldb = cp;
+    Out = a.Xb + (j * NB) * cp + (int64_t)k * NB; ldo = cp;
+  }
+
+  lq::Acc2x2 acc;
+  acc.clear();
+  for (int k0 = 0; k0 < NB; k0 += lq::RM_KT) {
+    lq::fill_rowmajor(sA, Aop + k0, lda, tid);
+    if (B_KMAJOR) lq::fill_kmajor32(sB, Bop + (int64_t)k0 * ldb, ldb, tid);
+    else lq::fill_rowmajor(sB, Bop + k0, ldb, tid);
+    __syncthreads();
+    lq::mma_chunk_rowmajor_a<B_KMAJOR>(sA, sB, wm, wn, lane, acc);
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        float* o = Out + (int64_t)lq::acc_row(wm, tm, v, lane) * ldo + lq::acc_col(wn, tn, lane);
+        if (SUBTRACT) *o -= acc.t[tm][tn][v];
+        else *o = acc.t[tm][tn][v];
+      }
+}
+
+// d[c-1-q] = sum_{p=q}^{c-1} Xb[p][q]^2 : column norms of L^-1 = diag(H_d^-1) reversed.
+__global__ __launch_bounds__(256) void colnorm_kernel(const float* __restrict__ Xb, int64_t cp,
+                                                      int64_t c, float* __restrict__ d) {
+  int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= c) return;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int64_t p = q;
+  for (; p + 3 < c; p += 4) {
+    float x0 = Xb[p * cp + q], x1 = Xb[(p + 1) * cp + q];
+    float x2 = Xb[(p + 2) * cp + q], x3 = Xb[(p + 3) * cp + q];
+    s0 += x0 * x0; s1 += x1 * x1; s2 += x2 * x2; s3 += x3 * x3;
+  }
+  for (; p < c; ++p) { float x = Xb[p * cp + q]; s0 += x * x; }
+  d[c - 1 - q] = (s0 + s1) + (s2 + s3);
+}
+
+// U[a][b] = Xb[c-1-a][c-1-b] for b >= a, else 0.
+__global__ __launch_bounds__(256) void flip_out_kernel(const float* __restrict__ Xb, int64_t cp,
+                                                       int64_t c, float* __restrict__ U, int64_t ldu) {
+  int64_t a = blockIdx.y;
+  int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (b >= c) return;
+  U[a * ldu + b] = (b >= a) ? Xb[(c - 1 - a) * cp + (c - 1 - b)] : 0.0f;
+}
+
+struct CholPlan {
+  int64_t cp;
+  int nb;
+  size_t off_A, off_X, off_D, off_S, total;
+};
+
+CholPlan make_plan(int64_t c) {
+  CholPlan p;
+  p.nb = (int)lq::ceil_div(c, NB);
+  p.cp = (int64_t)p.nb * NB;
+  size_t mat = (size_t)p.cp * p.cp * sizeof(float);
+  p.off_A = 0;
+  p.off_X = lq::align_up(mat, 256);
+  p.off_D = p.off_X + lq::align_up(mat, 256);
+  p.off_S = p.off_D + (size_t)p.nb * NB * NB * sizeof(float);
+  p.total = p.off_S + 256;
+  return p;
+}
+
+}  // namespace
+
+namespace lq {
+size_t cholesky_workspace_bytes(int64_t c) { return make_plan(c).total; }
+}  // namespace lq
+
+extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, float damp, float* U,
+                                     int64_t ldu, float* hinv_diag, int32_t* info, void* ws,
+                                     size_t ws_bytes, void* stream) {
+  if (!H || !U || !hinv_diag || !info) return lq::fail(LQ_ERR_INVALID_ARG, "lq_cholesky_inv: null pointer");
+  if (c < 1 || ldh < c || ldu < c) return lq::fail(LQ_ERR_INVALID_ARG, "lq_cholesky_inv: c=%lld ldh=%lld ldu=%lld", (long long)c, (long long)ldh, (long long)ldu);
+  if (!(damp >= 0.0f)) return lq::fail(LQ_ERR_INVALID_ARG, "lq_cholesky_inv: damp must be >= 0");
+  if (c > 65535) return lq::fail(LQ_ERR_UNSUPPORTED, "lq_cholesky_inv: c > 65535");
+  CholPlan plan = make_plan(c);
+  if (!ws || !lq::aligned(ws, 256) || ws_bytes < plan.total)
+    return lq::fail(LQ_ERR_WORKSPACE, "lq_cholesky_inv: workspace needs %zu bytes, 256-byte aligned", plan.total);
+
+  hipStream_t st = (hipStream_t)stream;
+  char* base = (char*)ws;
+  float* A = (float*)(base + plan.off_A);
+  float* Xb = (float*)(base + plan.off_X);
+  float* Dinv = (float*)(base + plan.off_D);
+  float* scal = (float*)(base + plan.off_S);
+  const int64_t cp = plan.cp;
+  const int nb = plan.nb;
+
+  const size_t potrf_lds = 2 * NB * DLD * sizeof(float);
+  static bool attr_done = false;
+  if (!attr_done) {
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)potrf_diag_kernel,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)potrf_lds));
+    attr_done = true;
+  }
+
+  hipLaunchKernelGGL(diag_mean_kernel, dim3(1), dim3(1024), 0, st, H, ldh, c, damp, scal, info);
+  LQ_CHECK_LAUNCH("diag_mean_kernel");
+  dim3 g2((unsigned)lq::ceil_div(cp, 256), (unsigned)cp);
+  hipLaunchKernelGGL(flip_damp_kernel, g2, dim3(256), 0, st, H, ldh, c, cp, (const float*)scal, A);
+  LQ_CHECK_LAUNCH("flip_damp_kernel");
+
+  ChArgs a;
+  a.A = A; a.Xb = Xb; a.Dinv = Dinv; a.cp = cp;
+  for (int kb = 0; kb < nb; ++kb) {
+    hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(256), potrf_lds, st, A, cp, kb, Dinv, info, c);
+    LQ_CHECK_LAUNCH("potrf_diag_kernel");
+    int m = nb - kb - 1;
+    if (m > 0) {
+      a.step = kb;
+      hipLaunchKernelGGL(chol_gemm_kernel<CH_PANEL>, dim3(m), dim3(WG_THREADS), 0, st, a);
+      LQ_CHECK_LAUNCH("chol_gemm_kernel<panel>");
+      hipLaunchKernelGGL(chol_gemm_kernel<CH_SYRK>, dim3(m * (m + 1) / 2), dim3(WG_THREADS), 0, st, a);
+      LQ_CHECK_LAUNCH("chol_gemm_kernel<syrk>");
+    }
+  }
+
+  int64_t n = cp * cp;
+  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)lq::ceil_div(n, 1024)), dim3(256), 0, st, Xb, n, 0.0f);
+  LQ_CHECK_LAUNCH("fill_kernel");
+  for (int i = 0; i < nb; ++i) {
+    a.step = i;
+    hipLaunchKernelGGL(chol_gemm_kernel<CH_TRI_ROW>, dim3(i + 1), dim3(WG_THREADS), 0, st, a);
+    LQ_CHECK_LAUNCH("chol_gemm_kernel<tri_row>");
+    if (i + 1 < nb) {
+      hipLaunchKernelGGL(chol_gemm_kernel<CH_TRI_UPD>, dim3((nb - i - 1) * (i + 1)), dim3(WG_THREADS), 0, st, a);
+      LQ_CHECK_LAUNCH("chol_gemm_kernel<tri_upd>");
+    }
+  }
+
+  hipLaunchKernelGGL(colnorm_kernel, dim3((unsigned)lq::ceil_div(c, 256)), dim3(256), 0, st,
+                     (const float*)Xb, cp, c, hinv_diag);
+  LQ_CHECK_LAUNCH("colnorm_kernel");
+  dim3 g3((unsigned)lq::ceil_div(c, 256), (unsigned)c);
+  hipLaunchKernelGGL(flip_out_kernel, g3, dim3(256), 0, st, (const float*)Xb, cp, c, U, ldu);
+  LQ_CHECK_LAUNCH("flip_out_kernel");
+  return LQ_OK;
+}

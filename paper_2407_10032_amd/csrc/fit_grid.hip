@@ -1,0 +1,330 @@
+// lq_fit_grid: loss-error-aware grids (Algorithm 1 lines 5-9).
+//
+// Non-uniform (Eq. 5, init Eq. 6): one workgroup walks rows of W; a row's weights
+// and the importance weights live in registers (one HBM read of W), every Lloyd
+// iteration is compare-and-accumulate in registers/LDS, and the 2*2^b cluster sums
+// are reduced in a fixed order (double precision across threads).
+//
+// Affine (Eq. 7, t from Eq. 8): the candidate set {(t_min, t_max)} collapses to far
+// fewer distinct grids.  S depends only on s = t_min + t_max, and for a fixed s the
+// zero-point Z = -round(lo / S) takes every integer between its values at the two
+// ends of the t_min range (lo / S moves by less than one per step of t_min).  A grid
+// is fully described by (S, Z), so each distinct (s, Z) is scored once, in double
+// precision, and the smallest objective wins -- the same minimizer as the full
+// enumeration, at a few thousand instead of (t + 1)^2 evaluations per group.
+#include <math.h>
+
+#include "lq_common.h"
+
+namespace {
+
+constexpr int NT = 256;  // threads per workgroup
+
+// ------------------------------------------------------------ importance weights
+// omega_i = (d_i / min d)^-p in fp32 and fp64 (the common factor changes no argmin and
+// keeps the values inside fp32 range).
+__global__ __launch_bounds__(1024) void importance_kernel(const float* __restrict__ d, int64_t c,
+                                                          float p, float* __restrict__ om32,
+                                                          double* __restrict__ om64) {
+  __shared__ float red[1024];
+  float m = INFINITY;
+  for (int64_t i = threadIdx.x; i < c; i += 1024) m = fminf(m, d[i]);
+  red[threadIdx.x] = m;
+  __syncthreads();
+  for (int w = 512; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] = fminf(red[threadIdx.x], red[threadIdx.x + w]);
+    __syncthreads();
+  }
+  const double dmin = (double)red[0];
+  for (int64_t i = threadIdx.x; i < c; i += 1024) {
+    double o = pow((double)d[i] / dmin, -(double)p);
+    om64[i] = o;
+    om32[i] = (float)o;
+  }
+}
+
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ------------------------------------------------------------ non-uniform: weighted Lloyd
+template <int K, int EPT>
+__global__ __launch_bounds__(NT) void kmeans_rows_kernel(const float* __restrict__ W, int64_t r,
+                                                         int64_t c, int64_t ldw,
+                                                         const float* __restrict__ om32,
+                                                         int max_iter, float* __restrict__ G) {
+  constexpr int ACC_LD = 2 * K + 1;
+  constexpr int PARTS = NT / (2 * K);   // threads that share one column of the reduction
+  constexpr int RPP = NT / PARTS;       // accumulator rows per part (= 2K)
+  __shared__ float sAcc[NT * ACC_LD];
+  __shared__ double sSum[2 * K];
+  __shared__ float sG[K];
+  __shared__ float sRed[8];
+  __shared__ int sChanged[2];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+  float om[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    int64_t col = (int64_t)e * NT + tid;
+    om[e] = (col < c) ? om32[col] : 0.0f;
+  }
+
+  for (int64_t row = blockIdx.x; row < r; row += gridDim.x) {
+    float w[EPT];
+    float lo = INFINITY, hi = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      int64_t col = (int64_t)e * NT + tid;
+      if (col < c) {
+        w[e] = W[row * ldw + col];
+        lo = fminf(lo, w[e]);
+        hi = fmaxf(hi, w[e]);
+      } else {
+        w[e] = 0.0f;
+      }
+    }
+    lo = wave_min(lo);
+    hi = wave_max(hi);
+    if (lane == 0) { sRed[wave] = lo; sRed[4 + wave] = hi; }
+    if (tid == 0) { sChanged[0] = 0; sChanged[1] = 0; }
+    __syncthreads();
+    lo = fminf(fminf(sRed[0], sRed[1]), fminf(sRed[2], sRed[3]));
+    hi = fmaxf(fmaxf(sRed[4], sRed[5]), fmaxf(sRed[6], sRed[7]));
+    // Eq. 6: evenly spaced initial grid from min to max
+    if (tid < K) sG[tid] = lo + (hi - lo) / (float)(K - 1) * (float)tid;
+    __syncthreads();
+
+    for (int it = 0; it < max_iter; ++it) {
+      float mid[K - 1];
+#pragma unroll
+      for (int m = 0; m < K - 1; ++m) mid[m] = 0.5f * (sG[m] + sG[m + 1]);
+      float* mine = sAcc + tid * ACC_LD;
+#pragma unroll
+      for (int m = 0; m < 2 * K; ++m) mine[m] = 0.0f;
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        int64_t col = (int64_t)e * NT + tid;
+        if (col < c) {
+          int idx = 0;
+#pragma unroll
+          for (int m = 0; m < K - 1; ++m) idx += (w[e] > mid[m]) ? 1 : 0;
+          mine[idx] += om[e] * w[e];
+          mine[K + idx] += om[e];
+        }
+      }
+      __syncthreads();
+      {
+        // column sums of the NT x 2K accumulator array, fixed order, in double
+        const int colm = tid / PARTS, part = tid % PARTS;
+        double s = 0.0;
+        for (int q = 0; q < RPP; ++q) s += (double)sAcc[(part * RPP + q) * ACC_LD + colm];
+#pragma unroll
+        for (int o = PARTS / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+        if (part == 0) sSum[colm] = s;
+      }
+      __syncthreads();
+      if (tid < K) {
+        double den = sSum[K + tid];
+        float old = sG[tid];
+        float gn = (den > 0.0) ? (float)(sSum[tid] / den) : old;
+        if (gn != old) sChanged[it & 1] = 1;
+        sG[tid] = gn;
+      }
+      __syncthreads();
+      const int changed = sChanged[it & 1];
+      if (tid == 0) sChanged[(it + 1) & 1] = 0;
+      if (!changed) break;
+    }
+    if (tid < K) G[row * K + tid] = sG[tid];
+    __syncthreads();
+  }
+}
+
+// ------------------------------------------------------------ affine: search of Eq. 7
+struct AffBest {
+  double loss;
+  int key;   // position of the class's first member in (t_min, t_max) lexicographic order
+  double S, Z;
+};
+
+__device__ __forceinline__ bool aff_better(double l, int k, const AffBest& b) {
+  return (l < b.loss) || (l == b.loss && k < b.key);
+}
+
+__global__ __launch_bounds__(NT) void affine_search_kernel(const float* __restrict__ W, int64_t c,
+                                                           int64_t ldw, int g, int ngroups,
+                                                           const double* __restrict__ om64, int bits,
+                                                           int T, int t, float* __restrict__ SZ) {
+  extern __shared__ __align__(16) unsigned char smraw[];
+  double* sOm = reinterpret_cast<double*>(smraw);          // [g]
+  double* sW = sOm + g;                                    // [g]
+  __shared__ float sRed[8];
+  __shared__ double sBestLoss[NT];
+  __shared__ int sBestKey[NT];
+  __shared__ double sBestS[NT], sBestZ[NT];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t row = blockIdx.x / ngroups;
+  const int gi = blockIdx.x % ngroups;
+  const float* wsrc = W + row * ldw + (int64_t)gi * g;
+
+  float lo = INFINITY, hi = -INFINITY;
+  for (int i = tid; i < g; i += NT) {
+    float x = wsrc[i];
+    sW[i] = (double)x;
+    sOm[i] = om64[(int64_t)gi * g + i];
+    lo = fminf(lo, x);
+    hi = fmaxf(hi, x);
+  }
+  lo = wave_min(lo);
+  hi = wave_max(hi);
+  if (lane == 0) { sRed[wave] = lo; sRed[4 + wave] = hi; }
+  __syncthreads();
+  const double lo0 = (double)fminf(fminf(sRed[0], sRed[1]), fminf(sRed[2], sRed[3]));
+  const double hi0 = (double)fmaxf(fmaxf(sRed[4], sRed[5]), fmaxf(sRed[6], sRed[7]));
+  const double R = hi0 - lo0;
+  float* out = SZ + (row * ngroups + gi) * 2;
+  if (R == 0.0) {  // constant group
+    if (tid == 0) { out[0] = 1.0f; out[1] = 0.0f; }
+    return;
+  }
+  const double qmax = (double)((1 << bits) - 1);
+  const double dT = (double)T;
+
+  AffBest best;
+  best.loss = INFINITY; best.key = 0x7fffffff; best.S = 1.0; best.Z = 0.0;
+  for (int s = tid; s <= 2 * t; s += NT) {
+    const int ta = (s > t) ? (s - t) : 0;      // smallest t_min with t_max = s - t_min <= t
+    const int tb = (s < t) ? s : t;            // largest t_min
+    const double lo_a = lo0 + (double)ta * R / dT;
+    const double hi_a = hi0 - (double)(s - ta) * R / dT;
+    const double S = (hi_a - lo_a) / qmax;
+    const double invS = 1.0 / S;
+    const double lo_b = lo0 + (double)tb * R / dT;
+    if (!(S > 0.0)) continue;                  // s == T: the range has shrunk to nothing
+    const double zf = -rint(lo_a / S);
+    const double zl = -rint(lo_b / S);
+    // lo / S moves by at most 2^b - 1 over the whole t_min range, so the class count is small
+    double span = zf - zl;
+    if (!(span >= 0.0)) span = 0.0;
+    const int nz = (int)fmin(span, 63.0) + 1;
+    for (int zi = 0; zi < nz; ++zi) {
+      const double Z = zf - (double)zi;
+      const double cl = -Z, ch = qmax - Z;
+      double loss = 0.0;
+      for (int i = 0; i < g; ++i) {
+        double w = sW[i];
+        double u = fmin(fmax(rint(w * invS), cl), ch);
+        double dlt = fma(u, S, -w);
+        loss = fma(sOm[i] * dlt, dlt, loss);
+      }
+      // first t_min of this class: smallest t_min >= ta with round(lo / S) == -Z
+      int tf = ta;
+      if (Z != zf) {
+        double x = ((-Z - 0.5) * S - lo0) * dT / R;
+        tf = (int)ceil(x);
+        if (tf < ta) tf = ta;
+        if (tf > tb) tf = tb;
+      }
+      const int key = tf * (t + 1) + (s - tf);
+      if (aff_better(loss, key, best)) { best.loss = loss; best.key = key; best.S = S; best.Z = Z; }
+    }
+  }
+  sBestLoss[tid] = best.loss; sBestKey[tid] = best.key; sBestS[tid] = best.S; sBestZ[tid] = best.Z;
+  __syncthreads();
+  for (int w2 = NT / 2; w2 > 0; w2 >>= 1) {
+    if (tid < w2) {
+      AffBest o;
+      o.loss = sBestLoss[tid]; o.key = sBestKey[tid];
+      if (aff_better(sBestLoss[tid + w2], sBestKey[tid + w2], o)) {
+        sBestLoss[tid] = sBestLoss[tid + w2]; sBestKey[tid] = sBestKey[tid + w2];
+        sBestS[tid] = sBestS[tid + w2]; sBestZ[tid] = sBestZ[tid + w2];
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) { out[0] = (float)sBestS[0]; out[1] = (float)sBestZ[0]; }
+}
+
+template <int K>
+lq_status launch_kmeans(const float* W, int64_t r, int64_t c, int64_t ldw, const float* om32,
+                        int max_iter, float* G, hipStream_t st) {
+  int64_t ept = lq::ceil_div(c, NT);
+  unsigned grid = (unsigned)(r < 2048 ? r : 2048);
+#define LQ_KM(E)                                                                              \
+  hipLaunchKernelGGL((kmeans_rows_kernel<K, E>), dim3(grid), dim3(NT), 0, st, W, r, c, ldw, \
+                     om32, max_iter, G)
+  if (ept <= 2) LQ_KM(2);
+  else if (ept <= 4) LQ_KM(4);
+  else if (ept <= 8) LQ_KM(8);
+  else if (ept <= 16) LQ_KM(16);
+  else if (ept <= 32) LQ_KM(32);
+  else if (ept <= 44) LQ_KM(44);
+  else LQ_KM(64);
+#undef LQ_KM
+  LQ_CHECK_LAUNCH("kmeans_rows_kernel");
+  return LQ_OK;
+}
+
+}  // namespace
+
+namespace lq {
+size_t fit_grid_workspace_bytes(int64_t c) {
+  return align_up((size_t)c * sizeof(double), 256) + align_up((size_t)c * sizeof(float), 256);
+}
+}  // namespace lq
+
+extern "C" lq_status lq_fit_grid(const float* W, int64_t r, int64_t c, int64_t ldw,
+                                 const float* hinv_diag, const lq_params* P, float* grid, void* ws,
+                                 size_t ws_bytes, void* stream) {
+  if (!W || !hinv_diag || !grid) return lq::fail(LQ_ERR_INVALID_ARG, "lq_fit_grid: null pointer");
+  if (r < 0 || c < 1 || ldw < c) return lq::fail(LQ_ERR_INVALID_ARG, "lq_fit_grid: r=%lld c=%lld ldw=%lld", (long long)r, (long long)c, (long long)ldw);
+  lq_status stt = lq::check_params(P, c);
+  if (stt != LQ_OK) return stt;
+  size_t need = lq::fit_grid_workspace_bytes(c);
+  if (!ws || !lq::aligned(ws, 256) || ws_bytes < need)
+    return lq::fail(LQ_ERR_WORKSPACE, "lq_fit_grid: workspace needs %zu bytes, 256-byte aligned", need);
+  if (r == 0) return LQ_OK;
+
+  hipStream_t st = (hipStream_t)stream;
+  double* om64 = (double*)ws;
+  float* om32 = (float*)((char*)ws + lq::align_up((size_t)c * sizeof(double), 256));
+
+  if (P->mode == LQ_GRID_NONUNIFORM) {
+    if (c > 64 * NT) return lq::fail(LQ_ERR_UNSUPPORTED, "lq_fit_grid: non-uniform fit supports c <= %d", 64 * NT);
+    hipLaunchKernelGGL(importance_kernel, dim3(1), dim3(1024), 0, st, hinv_diag, c, P->p, om32, om64);
+    LQ_CHECK_LAUNCH("importance_kernel");
+    switch (P->bits) {
+      case 2: return launch_kmeans<4>(W, r, c, ldw, om32, P->kmeans_max_iter, grid, st);
+      case 3: return launch_kmeans<8>(W, r, c, ldw, om32, P->kmeans_max_iter, grid, st);
+      default: return launch_kmeans<16>(W, r, c, ldw, om32, P->kmeans_max_iter, grid, st);
+    }
+  }
+
+  const int64_t g = P->group_size > 0 ? P->group_size : c;
+  if (g > 8192) return lq::fail(LQ_ERR_UNSUPPORTED, "lq_fit_grid: affine group of %lld columns (limit 8192)", (long long)g);
+  const int64_t ngroups = c / g;
+  if (r * ngroups > 0x7fffffffLL) return lq::fail(LQ_ERR_UNSUPPORTED, "lq_fit_grid: more than 2^31 groups");
+  hipLaunchKernelGGL(importance_kernel, dim3(1), dim3(1024), 0, st, hinv_diag, c, P->p, om32, om64);
+  LQ_CHECK_LAUNCH("importance_kernel");
+  const size_t lds = (size_t)g * 2 * sizeof(double);
+  static size_t lds_set = 0;
+  if (lds > lds_set) {
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)affine_search_kernel,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)(8192 * 16)));
+    lds_set = 8192 * 16;
+  }
+  hipLaunchKernelGGL(affine_search_kernel, dim3((unsigned)(r * ngroups)), dim3(NT), lds, st, W, c, ldw,
+                     (int)g, (int)ngroups, (const double*)om64, P->bits, P->T, lq::resolve_t(P), grid);
+  LQ_CHECK_LAUNCH("affine_search_kernel");
+  return LQ_OK;
+}

@@ -1,0 +1,94 @@
+// lq_hessian_accumulate: H += 2 X^T X  (Algorithm 1 line 3; Section 2.2, H = 2 X X^T
+// with the paper's X being channels x tokens).
+//
+// Symmetric rank-n update on fp32 MFMA: only the tiles on or above the diagonal
+// are computed.  The token range is cut into slices so that the launch has many
+// more workgroups than the chip has compute units; every (slice, tile) pair
+// writes a partial tile into the workspace and a second kernel adds the slices
+// in order into both triangles of H.
+#include "lq_common.h"
+#include "lq_tn_gemm.h"
+
+namespace {
+
+constexpr int KT = 32;                       // tokens per LDS stage
+constexpr int64_t MIN_TOKENS_PER_SPLIT = 256;
+constexpr int64_t TARGET_WORKGROUPS = 4096;  // >= 8 resident rounds of 2 workgroups per CU
+
+struct HessianPlan {
+  int T;        // tiles per dimension
+  int ntiles;   // tiles on or above the diagonal
+  int splits;
+  int64_t k_per_split;
+  size_t ws_bytes;
+};
+
+HessianPlan make_plan(int64_t c, int64_t n_tokens) {
+  HessianPlan p;
+  p.T = (int)lq::ceil_div(c, lq::TILE);
+  p.ntiles = p.T * (p.T + 1) / 2;
+  int64_t want = lq::ceil_div(TARGET_WORKGROUPS, p.ntiles);
+  int64_t most = n_tokens / MIN_TOKENS_PER_SPLIT;
+  if (most < 1) most = 1;
+  int64_t s = want < most ? want : most;
+  if (s < 1) s = 1;
+  int64_t per = lq::ceil_div(n_tokens > 0 ? n_tokens : 1, s);
+  per = lq::ceil_div(per, KT) * KT;
+  p.k_per_split = per;
+  p.splits = (int)lq::ceil_div(n_tokens > 0 ? n_tokens : 1, per);
+  p.ws_bytes = (size_t)p.splits * p.ntiles * lq::TILE * lq::TILE * sizeof(float);
+  return p;
+}
+
+}  // namespace
+
+namespace lq {
+size_t hessian_workspace_bytes(int64_t c, int64_t n_tokens) { return make_plan(c, n_tokens).ws_bytes; }
+}  // namespace lq
+
+extern "C" lq_status lq_hessian_accumulate(float* H, int64_t ldh, const float* X, int64_t n_tokens,
+                                           int64_t c, int64_t ldx, void* ws, size_t ws_bytes,
+                                           void* stream) {
+  if (!H || (!X && n_tokens > 0)) return lq::fail(LQ_ERR_INVALID_ARG, "lq_hessian_accumulate: null pointer");
+  if (c < 1 || n_tokens < 0) return lq::fail(LQ_ERR_INVALID_ARG, "lq_hessian_accumulate: c=%lld n_tokens=%lld", (long long)c, (long long)n_tokens);
+  if (ldh < c || ldx < c) return lq::fail(LQ_ERR_INVALID_ARG, "lq_hessian_accumulate: leading dimension smaller than c");
+  if (c > (int64_t)lq::TILE * 1024) return lq::fail(LQ_ERR_UNSUPPORTED, "lq_hessian_accumulate: c > 131072");
+  if (n_tokens == 0) return LQ_OK;
+  HessianPlan plan = make_plan(c, n_tokens);
+  if (!ws || !lq::aligned(ws, 256) || ws_bytes < plan.ws_bytes)
+    return lq::fail(LQ_ERR_WORKSPACE, "lq_hessian_accumulate: workspace needs %zu bytes, 256-byte aligned", plan.ws_bytes);
+
+  hipStream_t st = (hipStream_t)stream;
+  lq::TnGemmArgs a;
+  a.P = X; a.ldp = ldx;
+  a.Q = X; a.ldq = ldx;
+  a.C = H; a.ldc = ldh;
+  a.M = c; a.N = c; a.K = n_tokens;
+  a.alpha = 2.0f;
+  a.tiles_m = plan.T; a.tiles_n = plan.T;
+  a.ntiles = plan.ntiles;
+  a.splits = plan.splits;
+  a.k_per_split = plan.k_per_split;
+  a.partial = (float*)ws;
+
+  const bool vec = (ldx % 4 == 0) && lq::aligned(X, 16);
+  const size_t lds = 4 * KT * lq::TILE * sizeof(float);
+  dim3 grid((unsigned)((int64_t)plan.splits * plan.ntiles)), block(lq::WG_THREADS);
+  static bool attr_done = false;
+  if (!attr_done) {
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, true, true, true>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, true, true, false>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_done = true;
+  }
+  if (vec)
+    hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, true, true, true>), grid, block, lds, st, a);
+  else
+    hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, true, true, false>), grid, block, lds, st, a);
+  LQ_CHECK_LAUNCH("tn_gemm_kernel(hessian)");
+  hipLaunchKernelGGL(lq::tn_reduce_sym_kernel, dim3(plan.ntiles), block, 0, st, (const float*)ws,
+                     plan.splits, plan.ntiles, plan.T, H, ldh, c, 2.0f);
+  LQ_CHECK_LAUNCH("tn_reduce_sym_kernel");
+  return LQ_OK;
+}

@@ -1,0 +1,42 @@
+// Shared host-side helpers of the LeanQuant HIP library: error text, argument
+// checks, launch checks.  No device code and no arithmetic of the method here.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "../../include/leanquant.h"
+
+namespace lq {
+
+// Thread-local error text returned by lq_last_error().
+char* error_buffer();
+lq_status fail(lq_status code, const char* fmt, ...);
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Resolve Eq. 8's shrink limit t for the given parameters; returns < 0 if invalid.
+int resolve_t(const lq_params* P);
+// Validate the fields every call shares; returns LQ_OK or sets the error text.
+lq_status check_params(const lq_params* P, int64_t c);
+
+}  // namespace lq
+
+#define LQ_CHECK_HIP(expr)                                                                   \
+  do {                                                                                       \
+    hipError_t _e = (expr);                                                                  \
+    if (_e != hipSuccess)                                                                    \
+      return lq::fail(LQ_ERR_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e),     \
+                      __FILE__, __LINE__);                                                   \
+  } while (0)
+
+#define LQ_CHECK_LAUNCH(name)                                                                \
+  do {                                                                                       \
+    hipError_t _e = hipGetLastError();                                                       \
+    if (_e != hipSuccess)                                                                    \
+      return lq::fail(LQ_ERR_HIP, "launch of %s failed: %s", name, hipGetErrorString(_e));   \
+  } while (0)

@@ -1,0 +1,211 @@
+// C (+)= alpha * P^T Q on fp32 MFMA, with P [K x M] and Q [K x N] both k-major
+// (row index = contraction index), the shape shared by the two dense
+// contractions of Algorithm 1:
+//   line 3   H += 2 X^T X            P = Q = X (tokens x channels), symmetric
+//   line 19  W[:, i+B:] -= E U[...]  P = E^T stored as [B x r], Q = rows i..i+B of U
+//
+// A workgroup computes one 128 x 128 tile of C over a slice of the contraction
+// range.  Global loads of the next k-chunk are issued into registers before
+// the MFMAs of the current one and written to the other LDS buffer afterwards
+// (one barrier per chunk).  In symmetric mode only tiles on or above the
+// diagonal are computed; with a token split each slice writes a partial tile
+// that a second kernel sums in a fixed order and mirrors.
+#pragma once
+
+#include "lq_mfma.h"
+
+namespace lq {
+
+struct TnGemmArgs {
+  const float* P; int64_t ldp;
+  const float* Q; int64_t ldq;
+  float* C; int64_t ldc;
+  int64_t M, N, K;
+  float alpha;
+  int tiles_m, tiles_n;
+  int ntiles;           // tiles per split (upper-triangle count in symmetric mode)
+  int splits;
+  int64_t k_per_split;  // multiple of the k-chunk
+  float* partial;       // [splits][ntiles][128*128] when PARTIAL
+};
+
+// Upper-triangle tile enumeration, row by row: index -> (bi, bj), bj >= bi.
+__device__ __forceinline__ void decode_upper(int idx, int T, int& bi, int& bj) {
+  float tf = 2.0f * T + 1.0f;
+  int r = (int)((tf - sqrtf(tf * tf - 8.0f * (float)idx)) * 0.5f);
+  if (r < 0) r = 0;
+  if (r > T - 1) r = T - 1;
+  // start(r) = r*T - r*(r-1)/2
+  while (r > 0 && r * T - (r * (r - 1)) / 2 > idx) --r;
+  while (r + 1 < T && (r + 1) * T - ((r + 1) * r) / 2 <= idx) ++r;
+  bi = r;
+  bj = r + (idx - (r * T - (r * (r - 1)) / 2));
+}
+
+template <int KT, bool VEC>
+__device__ __forceinline__ void tn_load_chunk(const float* __restrict__ base, int64_t ld, int64_t k0,
+                                              int64_t kend, int64_t col0, int64_t ncols,
+                                              float4 (&r)[KT / 8], int tid) {
+#pragma unroll
+  for (int p = 0; p < KT / 8; ++p) {
+    int f = tid + p * WG_THREADS;
+    int64_t k = k0 + (f >> 5);
+    int64_t col = col0 + 4 * (f & 31);
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (k < kend) {
+      const float* src = base + k * ld + col;
+      if (VEC && col + 3 < ncols) {
+        v = *reinterpret_cast<const float4*>(src);
+      } else {
+        if (col + 0 < ncols) v.x = src[0];
+        if (col + 1 < ncols) v.y = src[1];
+        if (col + 2 < ncols) v.z = src[2];
+        if (col + 3 < ncols) v.w = src[3];
+      }
+    }
+    r[p] = v;
+  }
+}
+
+template <int KT>
+__device__ __forceinline__ void tn_store_chunk(float* __restrict__ s, const float4 (&r)[KT / 8],
+                                               int tid) {
+#pragma unroll
+  for (int p = 0; p < KT / 8; ++p) {
+    int f = tid + p * WG_THREADS;
+    *reinterpret_cast<float4*>(s + (f >> 5) * TILE + 4 * (f & 31)) = r[p];
+  }
+}
+
+template <int KT, bool SYM, bool PARTIAL, bool VEC>
+__global__ __launch_bounds__(WG_THREADS, 2) void tn_gemm_kernel(TnGemmArgs a) {
+  extern __shared__ __align__(16) float smem[];
+  constexpr int STAGE = KT * TILE;   // floats per operand per buffer; P buffers, then Q buffers
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  const int work = blockIdx.x;
+  const int split = work / a.ntiles;
+  const int tile = work - split * a.ntiles;
+  int bi, bj;
+  if (SYM) {
+    decode_upper(tile, a.tiles_m, bi, bj);
+  } else {
+    bi = tile / a.tiles_n;
+    bj = tile - bi * a.tiles_n;
+  }
+  const bool diag = SYM && (bi == bj);
+  const int64_t m0 = (int64_t)bi * TILE, n0 = (int64_t)bj * TILE;
+  const int64_t kbeg = (int64_t)split * a.k_per_split;
+  int64_t kend = kbeg + a.k_per_split;
+  if (kend > a.K) kend = a.K;
+
+  Acc2x2 acc;
+  acc.clear();
+
+  if (kbeg < kend) {
+    float4 rp[KT / 8], rq[KT / 8];
+    tn_load_chunk<KT, VEC>(a.P, a.ldp, kbeg, kend, m0, a.M, rp, tid);
+    if (!diag) tn_load_chunk<KT, VEC>(a.Q, a.ldq, kbeg, kend, n0, a.N, rq, tid);
+    tn_store_chunk<KT>(smem, rp, tid);
+    if (!diag) tn_store_chunk<KT>(smem + 2 * STAGE, rq, tid);
+    __syncthreads();
+    int buf = 0;
+    for (int64_t k0 = kbeg; k0 < kend; k0 += KT) {
+      const bool more = (k0 + KT) < kend;
+      if (more) {
+        tn_load_chunk<KT, VEC>(a.P, a.ldp, k0 + KT, kend, m0, a.M, rp, tid);
+        if (!diag) tn_load_chunk<KT, VEC>(a.Q, a.ldq, k0 + KT, kend, n0, a.N, rq, tid);
+      }
+      const float* cp = smem + buf * STAGE;
+      mma_chunk_kmajor<KT>(cp, diag ? cp : cp + 2 * STAGE, wm, wn, lane, acc);
+      if (more) {
+        float* np = smem + (buf ^ 1) * STAGE;
+        tn_store_chunk<KT>(np, rp, tid);
+        if (!diag) tn_store_chunk<KT>(np + 2 * STAGE, rq, tid);
+      }
+      __syncthreads();
+      buf ^= 1;
+    }
+  }
+
+  if (PARTIAL) {
+    float* out = a.partial + ((int64_t)split * a.ntiles + tile) * (TILE * TILE);
+#pragma unroll
+    for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          out[acc_row(wm, tm, v, lane) * TILE + acc_col(wn, tn, lane)] = acc.t[tm][tn][v];
+  } else {
+#pragma unroll
+    for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          int64_t row = m0 + acc_row(wm, tm, v, lane);
+          int64_t col = n0 + acc_col(wn, tn, lane);
+          if (row < a.M && col < a.N) {
+            float x = a.alpha * acc.t[tm][tn][v];
+            a.C[row * a.ldc + col] += x;
+            if (SYM && !diag) a.C[col * a.ldc + row] += x;
+          }
+        }
+  }
+}
+
+// Sum the token-split partial tiles in split order and add alpha * sum to C, writing
+// the tile at (bi, bj) and its transpose at (bj, bi).  One workgroup per upper tile.
+static __global__ __launch_bounds__(WG_THREADS) void tn_reduce_sym_kernel(const float* __restrict__ partial,
+                                                                  int splits, int ntiles, int T,
+                                                                  float* __restrict__ C, int64_t ldc,
+                                                                  int64_t M, float alpha) {
+  __shared__ float st[32 * 129];
+  const int tid = threadIdx.x;
+  const int tile = blockIdx.x;
+  int bi, bj;
+  decode_upper(tile, T, bi, bj);
+  const int64_t m0 = (int64_t)bi * TILE, n0 = (int64_t)bj * TILE;
+  for (int sb = 0; sb < 4; ++sb) {
+    // rows sb*32 .. sb*32+31 of the tile: 32 x 128 values, 16 per thread
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      int f = tid + p * WG_THREADS;  // float4 index within the 32 x 128 slab
+      int lr = f >> 5, c4 = f & 31;
+      const float* src = partial + (int64_t)tile * (TILE * TILE) + (sb * 32 + lr) * TILE + 4 * c4;
+      float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int sp = 0; sp < splits; ++sp) {
+        float4 v = *reinterpret_cast<const float4*>(src + (int64_t)sp * ntiles * (TILE * TILE));
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+      }
+      s.x *= alpha; s.y *= alpha; s.z *= alpha; s.w *= alpha;
+      int64_t row = m0 + sb * 32 + lr;
+      int64_t col = n0 + 4 * c4;
+      if (row < M) {
+        float* dst = C + row * ldc + col;
+        if (col + 0 < M) dst[0] += s.x;
+        if (col + 1 < M) dst[1] += s.y;
+        if (col + 2 < M) dst[2] += s.z;
+        if (col + 3 < M) dst[3] += s.w;
+      }
+      float* d = st + lr * 129 + 4 * c4;
+      d[0] = s.x; d[1] = s.y; d[2] = s.z; d[3] = s.w;
+    }
+    __syncthreads();
+    if (bi != bj) {
+      // transpose: target row n0 + lc, target columns m0 + sb*32 + (0..31)
+      const int lr = tid & 31;
+      for (int lc = tid >> 5; lc < TILE; lc += 8) {
+        int64_t row = n0 + lc;
+        int64_t col = m0 + sb * 32 + lr;
+        if (row < M && col < M) C[row * ldc + col] += st[lr * 129 + lc];
+      }
+    }
+    __syncthreads();
+  }
+}
+
+}  // namespace lq

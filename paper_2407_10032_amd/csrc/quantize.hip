@@ -1,0 +1,102 @@
+// lq_quantize_layer: the blocked quantize-and-propagate loop (Algorithm 1 lines 10-21).
+//
+// Rows of W are independent problems (Section 2.2), the only sequential dimension
+// is the column index.  Per block of B columns two kernels run:
+//   * the column kernel: one lane owns one row and keeps that row's B weights of the
+//     block in registers; for every column it quantizes against the row's grid
+//     (line 13 / 15), forms E = (w - q) / U_jj (line 16) and subtracts E * U[j, j+1:]
+//     from its remaining registers (line 17).  The B x B block of U is read from LDS at
+//     wave-uniform addresses.  E is written transposed ([B x r]) so that
+//   * the trailing update W[:, i+B:] -= E U[i:i+B, i+B:] (line 19) is a k-major
+//     fp32 MFMA product of the same kind as the Hessian accumulation.
+#include "lq_common.h"
+#include "lq_tn_gemm.h"
+
+#include "lq_quantize_col.h"
+
+namespace {
+
+constexpr int KT = 32;
+
+}  // namespace
+
+namespace lq {
+size_t quantize_workspace_bytes(int64_t r, int block) {
+  int64_t rpad = ceil_div(r > 0 ? r : 1, 64) * 64;
+  return (size_t)rpad * (size_t)(block > 0 ? block : 128) * sizeof(float);
+}
+}  // namespace lq
+
+extern "C" lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t ldw, const float* U,
+                                       int64_t ldu, const float* grid, const lq_params* P,
+                                       uint8_t* codes, float* row_loss, void* ws, size_t ws_bytes,
+                                       void* stream) {
+  if (!W || !U || !grid || !codes) return lq::fail(LQ_ERR_INVALID_ARG, "lq_quantize_layer: null pointer");
+  if (r < 0 || c < 1 || ldw < c || ldu < c)
+    return lq::fail(LQ_ERR_INVALID_ARG, "lq_quantize_layer: r=%lld c=%lld ldw=%lld ldu=%lld", (long long)r, (long long)c, (long long)ldw, (long long)ldu);
+  lq_status stt = lq::check_params(P, c);
+  if (stt != LQ_OK) return stt;
+  const int B = P->block;
+  if (B != 32 && B != 64 && B != 128)
+    return lq::fail(LQ_ERR_UNSUPPORTED, "lq_quantize_layer: block=%d (supported: 32, 64, 128)", B);
+  size_t need = lq::quantize_workspace_bytes(r, B);
+  if (!ws || !lq::aligned(ws, 256) || ws_bytes < need)
+    return lq::fail(LQ_ERR_WORKSPACE, "lq_quantize_layer: workspace needs %zu bytes, 256-byte aligned", need);
+  if (r == 0) return LQ_OK;
+
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t rpad = lq::ceil_div(r, 64) * 64;
+  lq::ColArgs a;
+  a.W = W; a.ldw = ldw; a.r = r; a.c = c;
+  a.U = U; a.ldu = ldu;
+  a.grid = grid;
+  a.group = (P->mode == LQ_GRID_AFFINE) ? (P->group_size > 0 ? P->group_size : (int)c) : (int)c;
+  a.ngroups = (int)(c / a.group);
+  a.codes = codes;
+  a.Et = (float*)ws; a.rpad = rpad;
+  a.row_loss = row_loss;
+  a.vecw = (ldw % 4 == 0) && lq::aligned(W, 16);
+
+  const size_t gemm_lds = 4 * KT * lq::TILE * sizeof(float);
+  static bool attr_done = false;
+  if (!attr_done) {
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, false, false, true>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds));
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, false, false, false>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds));
+    attr_done = true;
+  }
+
+  for (int64_t i0 = 0; i0 < c; i0 += B) {
+    a.i0 = i0;
+    a.nb = (int)((c - i0) < B ? (c - i0) : B);
+    a.first = (i0 == 0);
+    lq_status s2 = (B == 128) ? lq::launch_column_128(a, P, st)
+                 : (B == 64)  ? lq::launch_column_64(a, P, st)
+                              : lq::launch_column_32(a, P, st);
+    if (s2 != LQ_OK) return s2;
+    const int64_t rest = c - i0 - a.nb;
+    if (rest > 0) {
+      lq::TnGemmArgs t;
+      t.P = a.Et; t.ldp = rpad;
+      t.Q = U + i0 * ldu + (i0 + B); t.ldq = ldu;
+      t.C = W + (i0 + B); t.ldc = ldw;
+      t.M = r; t.N = rest; t.K = B;
+      t.alpha = -1.0f;
+      t.tiles_m = (int)lq::ceil_div(r, lq::TILE);
+      t.tiles_n = (int)lq::ceil_div(rest, lq::TILE);
+      t.ntiles = t.tiles_m * t.tiles_n;
+      t.splits = 1;
+      t.k_per_split = B;
+      t.partial = nullptr;
+      const bool vec = (ldu % 4 == 0) && lq::aligned(t.Q, 16);
+      dim3 grid2((unsigned)t.ntiles), block2(lq::WG_THREADS);
+      if (vec)
+        hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, false, false, true>), grid2, block2, gemm_lds, st, t);
+      else
+        hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, false, false, false>), grid2, block2, gemm_lds, st, t);
+      LQ_CHECK_LAUNCH("tn_gemm_kernel(trailing)");
+    }
+  }
+  return LQ_OK;
+}

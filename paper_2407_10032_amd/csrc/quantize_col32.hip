@@ -1,0 +1,8 @@
+// Column kernel instances for block width B = 32.
+#include "lq_quantize_col.h"
+
+namespace lq {
+lq_status launch_column_32(const ColArgs& a, const lq_params* P, hipStream_t st) {
+  return launch_column<32>(a, P, st);
+}
+}  // namespace lq

@@ -1,0 +1,8 @@
+// Column kernel instances for block width B = 64.
+#include "lq_quantize_col.h"
+
+namespace lq {
+lq_status launch_column_64(const ColArgs& a, const lq_params* P, hipStream_t st) {
+  return launch_column<64>(a, P, st);
+}
+}  // namespace lq

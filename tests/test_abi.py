@@ -1,0 +1,83 @@
+"""The C-ABI boundary without a GPU: the library loads, exports every symbol the header
+declares, sizes workspaces, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2407_10032_amd as lq
+from paper_2407_10032_amd import binding
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        pytest.fail("libleanquant.so is not built (python -m paper_2407_10032_amd.build)")
+    return lq.load()
+
+
+def test_exports_match_header(lib, repo_root):
+    text = open(os.path.join(repo_root, "include", "leanquant.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(lq_[a-z_]+)\s*\(", text))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_defaults_are_the_papers_settings():
+    P = lq.lq_params_default()
+    assert (P.bits, P.mode, P.group_size, P.block, P.T, P.t_override, P.kmeans_max_iter) == (4, 0, 0, 128, 2048, -1, 100)
+    assert P.damp == pytest.approx(0.01) and P.p == 4.0
+    assert lq.lq_version() == "0.1"
+
+
+def test_workspace_sizes():
+    P = lq.lq_params_default()
+    assert lq.lq_workspace_bytes(lq.LQ_CALL_HESSIAN, 0, 4096, 262144) == 8 * 528 * 128 * 128 * 4
+    assert lq.lq_workspace_bytes(lq.LQ_CALL_HESSIAN, 0, 16384, 65536) == 8256 * 128 * 128 * 4
+    assert lq.lq_workspace_bytes(lq.LQ_CALL_CHOLESKY, 0, 200) >= 2 * 256 * 256 * 4 + 2 * 128 * 128 * 4
+    assert lq.lq_workspace_bytes(lq.LQ_CALL_QUANTIZE, 100, 512, 0, P) == 128 * 128 * 4
+    assert lq.lq_workspace_bytes(lq.LQ_CALL_FIT_GRID, 10, 512, 0, P) >= 512 * 12
+    assert lq.lq_workspace_bytes(99, 1, 1, 1) == 0
+
+
+def _bad(status, fragment):
+    assert status != lq.LQ_OK
+    assert fragment in lq.lq_last_error()
+
+
+def test_argument_errors_are_host_side(lib):
+    P = lq.lq_params_default()
+    pp = ctypes.byref(P)
+    dummy = ctypes.c_void_p(256)   # never dereferenced: every call below fails before a launch
+    _bad(lib.lq_hessian_accumulate(None, 8, dummy, 4, 8, 8, dummy, 1 << 30, None), "null")
+    assert lib.lq_hessian_accumulate(dummy, 4, dummy, 4, 8, 8, dummy, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
+    assert lib.lq_hessian_accumulate(dummy, 8, dummy, 4, 8, 8, None, 0, None) == lq.LQ_ERR_WORKSPACE
+    assert lib.lq_hessian_accumulate(dummy, 8, dummy, 4, 8, 8, dummy, 16, None) == lq.LQ_ERR_WORKSPACE
+    assert lib.lq_hessian_accumulate(dummy, 8, dummy, 4, 8, 8, ctypes.c_void_p(260), 1 << 30, None) == lq.LQ_ERR_WORKSPACE
+    assert lib.lq_cholesky_inv(dummy, 8, 8, ctypes.c_float(-1.0), dummy, 8, dummy, dummy, dummy, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
+    assert lib.lq_cholesky_inv(dummy, 8, 8, ctypes.c_float(0.01), dummy, 4, dummy, dummy, dummy, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
+    assert lib.lq_cholesky_inv(dummy, 8, 8, ctypes.c_float(0.01), dummy, 8, dummy, dummy, dummy, 8, None) == lq.LQ_ERR_WORKSPACE
+    for field, value, frag in (("bits", 5, "bits"), ("bits", 1, "bits"), ("mode", 7, "mode"), ("block", 0, "block"),
+                               ("group_size", 64, "per row"), ("kmeans_max_iter", 0, "kmeans")):
+        Q = lq.lq_params_default(**{field: value})
+        _bad(lib.lq_fit_grid(dummy, 4, 512, 512, dummy, ctypes.byref(Q), dummy, dummy, 1 << 30, None), frag)
+    Q = lq.lq_params_default(mode=lq.LQ_GRID_AFFINE, group_size=100)
+    _bad(lib.lq_fit_grid(dummy, 4, 512, 512, dummy, ctypes.byref(Q), dummy, dummy, 1 << 30, None), "divide")
+    Q = lq.lq_params_default(mode=lq.LQ_GRID_AFFINE, t_override=2000)
+    _bad(lib.lq_fit_grid(dummy, 4, 512, 512, dummy, ctypes.byref(Q), dummy, dummy, 1 << 30, None), "t=")
+    assert lib.lq_fit_grid(dummy, 4, 512, 100, dummy, pp, dummy, dummy, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
+    assert lib.lq_fit_grid(dummy, 4, 20000, 20000, dummy, pp, dummy, dummy, 1 << 30, None) == lq.LQ_ERR_UNSUPPORTED
+    Q = lq.lq_params_default(block=100)
+    assert lib.lq_quantize_layer(dummy, 4, 512, 512, dummy, 512, dummy, ctypes.byref(Q), dummy, None, dummy, 1 << 30, None) == lq.LQ_ERR_UNSUPPORTED
+    assert lib.lq_quantize_layer(dummy, 4, 512, 512, dummy, 512, dummy, pp, None, None, dummy, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
+    assert lib.lq_quantize_layer(dummy, 4, 512, 512, dummy, 512, dummy, pp, dummy, None, dummy, 64, None) == lq.LQ_ERR_WORKSPACE
+
+
+def test_binding_rejects_cpu_tensors():
+    import torch
+    H = torch.zeros(4, 4)
+    with pytest.raises(TypeError):
+        lq.lq_hessian_accumulate(H, torch.zeros(2, 4), None)
