@@ -7,11 +7,13 @@
 //
 // Affine (Eq. 7, t from Eq. 8): the candidate set {(t_min, t_max)} collapses to far
 // fewer distinct grids.  S depends only on s = t_min + t_max, and for a fixed s the
-// zero-point Z = -round(lo / S) takes every integer between its values at the two
-// ends of the t_min range (lo / S moves by less than one per step of t_min).  A grid
-// is fully described by (S, Z), so each distinct (s, Z) is scored once, in double
-// precision, and the smallest objective wins -- the same minimizer as the full
-// enumeration, at a few thousand instead of (t + 1)^2 evaluations per group.
+// zero-point Z = -round(lo / S) is monotone in t_min.  A grid is fully described by
+// (S, Z), so each distinct (s, Z) is scored once, in double precision, and the
+// smallest objective wins -- the same minimizer as the full enumeration, at a few
+// thousand instead of (t + 1)^2 evaluations per group.  When lo / S moves by less
+// than one per step of t_min (T - 2t > 2^b - 1, as for T = 2048) the zero-points of a
+// given s are all integers between the two ends of the t_min range; for a coarser
+// partition the t_min range is walked and a grid scored whenever Z changes.
 #include <math.h>
 
 #include "lq_common.h"
@@ -202,41 +204,58 @@ __global__ __launch_bounds__(NT) void affine_search_kernel(const float* __restri
 
   AffBest best;
   best.loss = INFINITY; best.key = 0x7fffffff; best.S = 1.0; best.Z = 0.0;
+  // Objective of Eq. 7 for one grid (S, Z); key orders equal losses like the plain enumeration.
+  auto score = [&](double S, double Z, int key) {
+    const double invS = 1.0 / S;
+    const double cl = -Z, ch = qmax - Z;
+    double loss = 0.0;
+    for (int i = 0; i < g; ++i) {
+      double w = sW[i];
+      double u = fmin(fmax(rint(w * invS), cl), ch);
+      double dlt = fma(u, S, -w);
+      loss = fma(sOm[i] * dlt, dlt, loss);
+    }
+    if (aff_better(loss, key, best)) { best.loss = loss; best.key = key; best.S = S; best.Z = Z; }
+  };
+  // lo / S moves by (2^b - 1) / (T - s) per step of t_min.  When that is below one for every
+  // s (T - 2t > 2^b - 1, true for the paper's T = 2048) the zero-points reached for a given s
+  // are exactly the integers between the values at the two ends of the t_min range.
+  const bool dense = (double)(T - 2 * t) > qmax;
   for (int s = tid; s <= 2 * t; s += NT) {
     const int ta = (s > t) ? (s - t) : 0;      // smallest t_min with t_max = s - t_min <= t
     const int tb = (s < t) ? s : t;            // largest t_min
-    const double lo_a = lo0 + (double)ta * R / dT;
-    const double hi_a = hi0 - (double)(s - ta) * R / dT;
-    const double S = (hi_a - lo_a) / qmax;
-    const double invS = 1.0 / S;
-    const double lo_b = lo0 + (double)tb * R / dT;
-    if (!(S > 0.0)) continue;                  // s == T: the range has shrunk to nothing
-    const double zf = -rint(lo_a / S);
-    const double zl = -rint(lo_b / S);
-    // lo / S moves by at most 2^b - 1 over the whole t_min range, so the class count is small
-    double span = zf - zl;
-    if (!(span >= 0.0)) span = 0.0;
-    const int nz = (int)fmin(span, 63.0) + 1;
-    for (int zi = 0; zi < nz; ++zi) {
-      const double Z = zf - (double)zi;
-      const double cl = -Z, ch = qmax - Z;
-      double loss = 0.0;
-      for (int i = 0; i < g; ++i) {
-        double w = sW[i];
-        double u = fmin(fmax(rint(w * invS), cl), ch);
-        double dlt = fma(u, S, -w);
-        loss = fma(sOm[i] * dlt, dlt, loss);
+    if (dense) {
+      const double lo_a = lo0 + (double)ta * R / dT;
+      const double hi_a = hi0 - (double)(s - ta) * R / dT;
+      const double S = (hi_a - lo_a) / qmax;
+      if (!(S > 0.0)) continue;
+      const double lo_b = lo0 + (double)tb * R / dT;
+      const double zf = -rint(lo_a / S);
+      const double zl = -rint(lo_b / S);
+      double span = zf - zl;
+      if (!(span >= 0.0)) span = 0.0;
+      const int nz = (int)fmin(span, 63.0) + 1;
+      for (int zi = 0; zi < nz; ++zi) {
+        const double Z = zf - (double)zi;
+        // first t_min of this class: smallest t_min >= ta with round(lo / S) == -Z
+        int tf = ta;
+        if (zi > 0) {
+          tf = (int)ceil(((-Z - 0.5) * S - lo0) * dT / R);
+          tf = tf < ta ? ta : (tf > tb ? tb : tf);
+        }
+        score(S, Z, tf * (t + 1) + (s - tf));
       }
-      // first t_min of this class: smallest t_min >= ta with round(lo / S) == -Z
-      int tf = ta;
-      if (Z != zf) {
-        double x = ((-Z - 0.5) * S - lo0) * dT / R;
-        tf = (int)ceil(x);
-        if (tf < ta) tf = ta;
-        if (tf > tb) tf = tb;
+    } else {
+      double zprev = 0.0;
+      for (int tm = ta; tm <= tb; ++tm) {
+        const double lo_c = lo0 + (double)tm * R / dT;
+        const double hi_c = hi0 - (double)(s - tm) * R / dT;
+        const double S = (hi_c - lo_c) / qmax;
+        if (!(S > 0.0)) continue;
+        const double Z = -rint(lo_c / S);
+        if (tm == ta || Z != zprev) score(S, Z, tm * (t + 1) + (s - tm));
+        zprev = Z;
       }
-      const int key = tf * (t + 1) + (s - tf);
-      if (aff_better(loss, key, best)) { best.loss = loss; best.key = key; best.S = S; best.Z = Z; }
     }
   }
   sBestLoss[tid] = best.loss; sBestKey[tid] = best.key; sBestS[tid] = best.S; sBestZ[tid] = best.Z;
