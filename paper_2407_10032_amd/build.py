@@ -21,15 +21,21 @@ FLAGS = [
 ]
 
 
-def _newest_header() -> float:
-    return max(os.path.getmtime(os.path.join(d, f)) for d in (CSRC, os.path.join(HERE, "..", "include"))
-               for f in os.listdir(d) if f.endswith(".h"))
+_COL_HEADERS = ("lq_quantize_col.h", "lq_common.h")
+
+
+def _newest_header(src: str) -> float:
+    """Newest header the source can depend on (the column-kernel units use only two)."""
+    names = _COL_HEADERS if src.startswith("quantize_col") else tuple(
+        f for f in os.listdir(CSRC) if f.endswith(".h"))
+    paths = [os.path.join(CSRC, f) for f in names] + [os.path.join(HERE, "..", "include", "leanquant.h")]
+    return max(os.path.getmtime(p) for p in paths)
 
 
 def _compile(src: str, incremental: bool = False) -> str:
     obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
     if incremental and os.path.exists(obj):
-        if os.path.getmtime(obj) > max(os.path.getmtime(os.path.join(CSRC, src)), _newest_header()):
+        if os.path.getmtime(obj) > max(os.path.getmtime(os.path.join(CSRC, src)), _newest_header(src)):
             return obj
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)

@@ -68,15 +68,62 @@ __global__ __launch_bounds__(256) void fill_kernel(float* __restrict__ p, int64_
   }
 }
 
-// Factor the diagonal block kb in LDS (column by column), invert the factor, write
-// L_kk back (upper part zeroed) and its inverse to Dinv[kb] (128 x 128, ld 128).
+// ---------------------------------------------------------------- diagonal block
+// 32 x 32 tile product on one wavefront, operands in LDS:
+//   acc += sign * A * B,  A[m][k] = pa[m*lda + k],
+//   B[k][n] = B_TRANS ? pb[n*ldb + k] : pb[k*ldb + n],  k < 32.
+// Leading dimensions of row-read operands are odd (129, 33), so the reads are conflict-free.
+template <bool B_TRANS, bool NEGATE>
+__device__ __forceinline__ void tile32_mma(lq::floatx16& acc, const float* pa, int lda,
+                                           const float* pb, int ldb, int lane) {
+  const int ml = lane & 31, kl = lane >> 5;
+#pragma unroll
+  for (int kk = 0; kk < 16; ++kk) {
+    const int k = 2 * kk + kl;
+    float a = pa[ml * lda + k];
+    float b = B_TRANS ? pb[ml * ldb + k] : pb[k * ldb + ml];
+    if (NEGATE) a = -a;
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+  }
+}
+
+__device__ __forceinline__ void tile32_store(const lq::floatx16& acc, float* dst, int ld, int lane,
+                                             float scale) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v)
+    dst[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * ld + (lane & 31)] = scale * acc[v];
+}
+
+__device__ __forceinline__ void tile32_load(lq::floatx16& acc, const float* src, int ld, int lane) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v)
+    acc[v] = src[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * ld + (lane & 31)];
+}
+
+__device__ __forceinline__ float lane_bcast(float v, int src_lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
+}
+
+constexpr int XLD = 33;                 // leading dimension of a 32 x 32 block of the inverse
+constexpr int XBLK = 32 * XLD;
+__device__ __forceinline__ int xblk(int i, int k) { return (i * (i + 1) / 2 + k) * XBLK; }
+
+// Factor the 128 x 128 diagonal block kb and invert its factor, all in LDS, one
+// workgroup.  The block is processed as 4 sub-panels of 32 columns: wavefront 0
+// factors and inverts the 32 x 32 diagonal sub-block in registers (lane = row for the
+// factor, lane = column for the inverse; entries of other lanes come through
+// v_readlane), the sub-panel below it and the rest of the block are then updated with
+// 32 x 32 MFMA tiles.  The inverse of the whole factor is assembled block by block
+// from the inverted diagonal sub-blocks: X_ik = -X_ii * sum_{k<=m<i} L_im X_mk.
+// Writes L_kk back (upper part zeroed) and its inverse to Dinv[kb] (128 x 128, ld 128).
 __global__ __launch_bounds__(256) void potrf_diag_kernel(float* __restrict__ A, int64_t cp, int kb,
                                                          float* __restrict__ Dinv,
                                                          int32_t* __restrict__ info, int64_t c) {
   extern __shared__ __align__(16) float sm[];
-  float* sL = sm;                // [128][129]
-  float* sX = sm + NB * DLD;     // [128][129]
-  const int tid = threadIdx.x;
+  float* sL = sm;                       // [128][129]
+  float* sX = sm + NB * DLD;            // 10 lower blocks of the inverse, [32][33] each
+  float* sT = sX + 10 * XBLK;           // 3 temporaries, [32][33] each
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float* tile = A + ((int64_t)kb * NB) * cp + (int64_t)kb * NB;
   for (int f = tid; f < NB * NB / 4; f += 256) {
     int row = f >> 5, c4 = f & 31;
@@ -86,47 +133,106 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(float* __restrict__ A, 
   }
   __syncthreads();
 
-  const int ri = tid & 127, half = tid >> 7;
-  for (int j = 0; j < NB; ++j) {
-    float pv = sL[j * DLD + j];
-    if (!(pv > 0.0f)) {
-      int64_t q = (int64_t)kb * NB + j;
-      if (tid == 0 && q < c && *info == 0) *info = (int32_t)(c - 1 - q) + 1;
-      pv = 1.0f;
-    }
-    const float dj = sqrtf(pv);
-    const float rd = 1.0f / dj;
-    __syncthreads();  // everyone has read the pivot
-    if (half == 0) {
-      if (ri > j) sL[ri * DLD + j] *= rd;
-      else if (ri == j) sL[j * DLD + j] = dj;
+  for (int kk = 0; kk < 4; ++kk) {
+    const int c0 = kk * 32;
+    if (wave == 0) {
+      const int ri = lane & 31;
+      float a[32];
+#pragma unroll
+      for (int k = 0; k < 32; ++k) a[k] = sL[(c0 + ri) * DLD + c0 + k];
+      // right-looking Cholesky of the 32 x 32 sub-block, row ri in this lane
+#pragma unroll
+      for (int j = 0; j < 32; ++j) {
+        float pj = lane_bcast(a[j], j);
+        if (!(pj > 0.0f)) {
+          int64_t q = (int64_t)kb * NB + c0 + j;
+          if (lane == 0 && q < c && *info == 0) *info = (int32_t)(c - 1 - q) + 1;
+          pj = 1.0f;
+        }
+        const float dj = sqrtf(pj);
+        const float rj = 1.0f / dj;
+        a[j] = (ri == j) ? dj : a[j] * rj;
+#pragma unroll
+        for (int k = j + 1; k < 32; ++k) a[k] = fmaf(-a[j], lane_bcast(a[j], k), a[k]);
+      }
+      // inverse of the sub-block's factor, column ri in this lane
+      float x[32];
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int k = 0; k < i; ++k) acc = fmaf(lane_bcast(a[k], i), x[k], acc);
+        x[i] = ((ri == i) ? 1.0f : -acc) / lane_bcast(a[i], i);
+      }
+      if (lane < 32) {
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+          if (k <= ri) sL[(c0 + ri) * DLD + c0 + k] = a[k];
+          sX[xblk(kk, kk) + k * XLD + ri] = (k >= ri) ? x[k] : 0.0f;
+        }
+      }
     }
     __syncthreads();
-    if (ri > j) {
-      const float lij = sL[ri * DLD + j];
-      for (int k = j + 1 + half; k <= ri; k += 2) sL[ri * DLD + k] -= lij * sL[k * DLD + j];
+    // sub-panel: A[ib, kk] <- A[ib, kk] * inv(L_kk)^T for the 32-row blocks below
+    {
+      const int ib = kk + 1 + wave;
+      if (ib < 4) {
+        lq::floatx16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+        float* blk = sL + (ib * 32) * DLD + c0;
+        tile32_mma<true, false>(acc, blk, DLD, sX + xblk(kk, kk), XLD, lane);
+        tile32_store(acc, blk, DLD, lane, 1.0f);
+      }
+    }
+    __syncthreads();
+    // rest of the block: A[ib, jb] -= P_ib P_jb^T for kk < jb <= ib
+    {
+      const int m = 3 - kk;
+      const int ntile = m * (m + 1) / 2;
+      for (int t = wave; t < ntile; t += 4) {
+        int ii = (t >= 3) ? 2 : (t >= 1) ? 1 : 0;
+        int jj = t - ii * (ii + 1) / 2;
+        const int ib = kk + 1 + ii, jb = kk + 1 + jj;
+        float* ct = sL + (ib * 32) * DLD + jb * 32;
+        lq::floatx16 acc;
+        tile32_load(acc, ct, DLD, lane);
+        tile32_mma<true, true>(acc, sL + (ib * 32) * DLD + c0, DLD, sL + (jb * 32) * DLD + c0, DLD, lane);
+        tile32_store(acc, ct, DLD, lane, 1.0f);
+      }
     }
     __syncthreads();
   }
 
-  // X = L^-1, one column per thread (columns are independent).
-  if (tid < NB) {
-    const int j = tid;
-    for (int i = 0; i < j; ++i) sX[i * DLD + j] = 0.0f;
-    sX[j * DLD + j] = 1.0f / sL[j * DLD + j];
-    for (int i = j + 1; i < NB; ++i) {
-      float acc = 0.0f;
-      for (int k = j; k < i; ++k) acc += sL[i * DLD + k] * sX[k * DLD + j];
-      sX[i * DLD + j] = -acc / sL[i * DLD + i];
+  // inverse of the 128 x 128 factor from the inverted diagonal sub-blocks
+  for (int dist = 1; dist < 4; ++dist) {
+    const int k = wave, i = wave + dist;
+    const bool active = i < 4;
+    if (active) {
+      lq::floatx16 acc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+      for (int m = k; m < i; ++m)
+        tile32_mma<false, false>(acc, sL + (i * 32) * DLD + m * 32, DLD, sX + xblk(m, k), XLD, lane);
+      tile32_store(acc, sT + wave * XBLK, XLD, lane, 1.0f);
     }
+    __syncthreads();
+    if (active) {
+      lq::floatx16 acc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+      tile32_mma<false, false>(acc, sX + xblk(i, i), XLD, sT + wave * XBLK, XLD, lane);
+      tile32_store(acc, sX + xblk(i, k), XLD, lane, -1.0f);
+    }
+    __syncthreads();
   }
-  __syncthreads();
 
   float* dinv = Dinv + (int64_t)kb * NB * NB;
   for (int f = tid; f < NB * NB; f += 256) {
     int row = f >> 7, col = f & 127;
     tile[(int64_t)row * cp + col] = (col <= row) ? sL[row * DLD + col] : 0.0f;
-    dinv[f] = sX[row * DLD + col];
+    int ib = row >> 5, jb = col >> 5;
+    dinv[f] = (jb <= ib) ? sX[xblk(ib, jb) + (row & 31) * XLD + (col & 31)] : 0.0f;
   }
 }
 
@@ -218,19 +324,28 @@ __global__ __launch_bounds__(WG_THREADS, 2) void chol_gemm_kernel(ChArgs a) {
 }
 
 // d[c-1-q] = sum_{p=q}^{c-1} Xb[p][q]^2 : column norms of L^-1 = diag(H_d^-1) reversed.
+// 32 columns per workgroup, 8 row-strided partial sums per column added in a fixed order.
 __global__ __launch_bounds__(256) void colnorm_kernel(const float* __restrict__ Xb, int64_t cp,
                                                       int64_t c, float* __restrict__ d) {
-  int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (q >= c) return;
-  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-  int64_t p = q;
-  for (; p + 3 < c; p += 4) {
-    float x0 = Xb[p * cp + q], x1 = Xb[(p + 1) * cp + q];
-    float x2 = Xb[(p + 2) * cp + q], x3 = Xb[(p + 3) * cp + q];
-    s0 += x0 * x0; s1 += x1 * x1; s2 += x2 * x2; s3 += x3 * x3;
+  __shared__ float part[8][33];
+  const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
+  const int64_t q = (int64_t)blockIdx.x * 32 + cx;
+  float s = 0.0f;
+  if (q < c) {
+    const int64_t p0 = (int64_t)blockIdx.x * 32;   // rows above the block's first column are zero
+    for (int64_t p = p0 + ry; p < c; p += 8) {
+      float x = (p >= q) ? Xb[p * cp + q] : 0.0f;
+      s = fmaf(x, x, s);
+    }
   }
-  for (; p < c; ++p) { float x = Xb[p * cp + q]; s0 += x * x; }
-  d[c - 1 - q] = (s0 + s1) + (s2 + s3);
+  part[ry][cx] = s;
+  __syncthreads();
+  if (ry == 0 && q < c) {
+    float t = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t += part[k][cx];
+    d[c - 1 - q] = t;
+  }
 }
 
 // U[a][b] = Xb[c-1-a][c-1-b] for b >= a, else 0.
@@ -287,7 +402,7 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
   const int64_t cp = plan.cp;
   const int nb = plan.nb;
 
-  const size_t potrf_lds = 2 * NB * DLD * sizeof(float);
+  const size_t potrf_lds = (NB * DLD + 13 * 32 * 33) * sizeof(float);
   static bool attr_done = false;
   if (!attr_done) {
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)potrf_diag_kernel,
@@ -329,7 +444,7 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
     }
   }
 
-  hipLaunchKernelGGL(colnorm_kernel, dim3((unsigned)lq::ceil_div(c, 256)), dim3(256), 0, st,
+  hipLaunchKernelGGL(colnorm_kernel, dim3((unsigned)lq::ceil_div(c, 32)), dim3(256), 0, st,
                      (const float*)Xb, cp, c, hinv_diag);
   LQ_CHECK_LAUNCH("colnorm_kernel");
   dim3 g3((unsigned)lq::ceil_div(c, 256), (unsigned)c);

@@ -11,9 +11,11 @@
 
 namespace {
 
-constexpr int KT = 32;                       // tokens per LDS stage
+constexpr int KT = 16;                       // tokens per LDS stage: 32 KB of LDS and < 128 VGPRs,
+                                             // so four workgroups share a compute unit
+constexpr int MINW = 3;
 constexpr int64_t MIN_TOKENS_PER_SPLIT = 256;
-constexpr int64_t TARGET_WORKGROUPS = 4096;  // >= 8 resident rounds of 2 workgroups per CU
+constexpr int64_t TARGET_WORKGROUPS = 16384; // ~32 resident rounds of 2 workgroups per CU: short tail
 
 struct HessianPlan {
   int T;        // tiles per dimension
@@ -76,16 +78,16 @@ extern "C" lq_status lq_hessian_accumulate(float* H, int64_t ldh, const float* X
   dim3 grid((unsigned)((int64_t)plan.splits * plan.ntiles)), block(lq::WG_THREADS);
   static bool attr_done = false;
   if (!attr_done) {
-    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, true, true, true>,
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, true, true, true, MINW>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, true, true, false>,
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, true, true, false, MINW>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_done = true;
   }
   if (vec)
-    hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, true, true, true>), grid, block, lds, st, a);
+    hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, true, true, true, MINW>), grid, block, lds, st, a);
   else
-    hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, true, true, false>), grid, block, lds, st, a);
+    hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, true, true, false, MINW>), grid, block, lds, st, a);
   LQ_CHECK_LAUNCH("tn_gemm_kernel(hessian)");
   hipLaunchKernelGGL(lq::tn_reduce_sym_kernel, dim3(plan.ntiles), block, 0, st, (const float*)ws,
                      plan.splits, plan.ntiles, plan.T, H, ldh, c, 2.0f);

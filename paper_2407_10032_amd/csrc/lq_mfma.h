@@ -47,16 +47,24 @@ __device__ __forceinline__ void mma_chunk_kmajor(const float* __restrict__ sP,
                                                  const float* __restrict__ sQ, int wm, int wn,
                                                  int lane, Acc2x2& acc) {
   const int kl = lane >> 5, ml = lane & 31;
+  const float* p = sP + kl * TILE + wm * 64 + ml;   // + 2*kk*TILE per step: immediate offsets
+  const float* q = sQ + kl * TILE + wn * 64 + ml;
+  // operands of step kk+1 are read while the MFMAs of step kk run
+  float a0[2], a1[2], b0[2], b1[2];
+  a0[0] = p[0]; a1[0] = p[32]; b0[0] = q[0]; b1[0] = q[32];
 #pragma unroll
   for (int kk = 0; kk < KT / 2; ++kk) {
-    const float* p = sP + (2 * kk + kl) * TILE + wm * 64 + ml;
-    const float* q = sQ + (2 * kk + kl) * TILE + wn * 64 + ml;
-    float a0 = p[0], a1 = p[32];
-    float b0 = q[0], b1 = q[32];
-    acc.t[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc.t[0][0], 0, 0, 0);
-    acc.t[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc.t[0][1], 0, 0, 0);
-    acc.t[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc.t[1][0], 0, 0, 0);
-    acc.t[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc.t[1][1], 0, 0, 0);
+    const int cur = kk & 1, nxt = cur ^ 1;
+    if (kk + 1 < KT / 2) {
+      a0[nxt] = p[2 * (kk + 1) * TILE];
+      a1[nxt] = p[2 * (kk + 1) * TILE + 32];
+      b0[nxt] = q[2 * (kk + 1) * TILE];
+      b1[nxt] = q[2 * (kk + 1) * TILE + 32];
+    }
+    acc.t[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[cur], b0[cur], acc.t[0][0], 0, 0, 0);
+    acc.t[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[cur], b1[cur], acc.t[0][1], 0, 0, 0);
+    acc.t[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[cur], b0[cur], acc.t[1][0], 0, 0, 0);
+    acc.t[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[cur], b1[cur], acc.t[1][1], 0, 0, 0);
   }
 }
 

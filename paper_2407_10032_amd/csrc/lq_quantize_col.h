@@ -1,105 +1,159 @@
-// Column kernel of lq_quantize_layer (Algorithm 1 lines 11-18): one lane owns one row
-// and keeps that row's B weights of the current block in registers; for every column
-// it quantizes against the row's grid (line 13 / 15), forms E = (w - q) / U_jj (line 16)
-// and subtracts E * U[j, j+1:] from its remaining registers (line 17).  The B x B block
-// of U is read from LDS at wave-uniform addresses.  E is written transposed ([B x r]) for
-// the trailing MFMA update.  Instantiated per block width in separate translation units.
+// Column kernel of lq_quantize_layer (Algorithm 1 lines 11-18) for one block of B columns.
+//
+// A wavefront owns 64 rows of W; its 64 x B piece of the block lives in LDS for the
+// whole kernel.  The block is processed in sub-blocks of 32 columns:
+//   * the sub-block's columns are pulled into registers with one lane per row, and the
+//     32 columns are handled in order: quantize against the row's grid (line 13 / 15),
+//     E = (w - q) / U_jj (line 16), subtract E * U[j, j+1:] inside the sub-block
+//     (line 17) with U read from LDS at wave-uniform addresses;
+//   * the rest of line 17, the update of the block's later columns by the sub-block's 32
+//     error columns, is a 64 x 32 by 32 x (up to 96) product done on fp32 MFMA straight
+//     on the LDS-resident piece (the A operand is built from the per-lane errors with a
+//     cross-half lane exchange, the B operand comes from the packed U block).
+// The code of one sub-block is a few thousand instructions and is reused by a run-time
+// loop, so the kernel stays inside the instruction cache.  E is written transposed
+// ([B x r]) for the trailing update across blocks.  The B x B diagonal blocks of U are
+// packed, zero-padded, by a small kernel once per layer.
 #pragma once
 
 #include "lq_common.h"
+#include "lq_mfma.h"
 
 namespace lq {
 
-constexpr int QT = 256;  // threads (= rows) per workgroup of the column kernel
+constexpr int QT = 256;   // threads per workgroup = rows per workgroup (4 wavefronts x 64 rows)
+constexpr int SB = 32;    // sub-block width
 
 struct ColArgs {
   float* W; int64_t ldw;
   int64_t r, c;
   int64_t i0;           // first column of the block
   int nb;               // columns in this block (<= B)
-  const float* U; int64_t ldu;
   const float* grid;    // nu: [r x K]; aff: [r x ngroups x 2]
   int group; int ngroups;
   uint8_t* codes;
   float* Et; int64_t rpad;
   float* row_loss;      // may be null
   int first;            // 1 for the first block (row_loss starts from zero)
-  int vecw;             // W rows may be read / written as float4
+  int vecw;             // W rows are 16-byte aligned (ldw % 4 == 0)
 };
 
-// Nearest point of an ascending grid; ties go to the lower point.
-template <int K>
-__device__ __forceinline__ void quant_nu(float w, const float (&g)[K], const float (&mid)[K - 1],
-                                         float& q, int& code) {
-  q = g[0];
-  code = 0;
-#pragma unroll
-  for (int m = 1; m < K; ++m) {
-    bool up = w > mid[m - 1];
-    q = up ? g[m] : q;
-    code += up ? 1 : 0;
-  }
+// Nearest point of an ascending grid; ties go to the lower point.  code = number of
+// midpoints below w, found by bisection: each level compares with the middle candidate
+// and keeps the half of the midpoints and grid points that is still possible.  The
+// candidates travel as vector values (halved by .lo / .hi), which keeps them in registers
+// and needs one comparison mask per level.
+typedef float f2v __attribute__((ext_vector_type(2)));
+typedef float f4v __attribute__((ext_vector_type(4)));
+typedef float f8v __attribute__((ext_vector_type(8)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+template <int K> struct GridVec;
+template <> struct GridVec<4> { typedef f4v type; };
+template <> struct GridVec<8> { typedef f8v type; };
+template <> struct GridVec<16> { typedef f16v type; };
+
+// g: the K grid points; m: the K - 1 midpoints in elements 0..K-2 (element K-1 unused).
+__device__ __forceinline__ void quant_nu_vec(float w, f2v g, f2v m, float& q, int& code) {
+  const bool up = w > m.x;
+  q = up ? g.y : g.x;
+  code = up ? 1 : 0;
+}
+__device__ __forceinline__ void quant_nu_vec(float w, f4v g, f4v m, float& q, int& code) {
+  const bool up = w > m.y;
+  int c;
+  quant_nu_vec(w, up ? g.hi : g.lo, up ? m.hi : m.lo, q, c);
+  code = c + (up ? 2 : 0);
+}
+__device__ __forceinline__ void quant_nu_vec(float w, f8v g, f8v m, float& q, int& code) {
+  const bool up = w > m.s3;
+  int c;
+  quant_nu_vec(w, up ? g.hi : g.lo, up ? m.hi : m.lo, q, c);
+  code = c + (up ? 4 : 0);
+}
+__device__ __forceinline__ void quant_nu_vec(float w, f16v g, f16v m, float& q, int& code) {
+  const bool up = w > m.s7;
+  int c;
+  quant_nu_vec(w, up ? g.hi : g.lo, up ? m.hi : m.lo, q, c);
+  code = c + (up ? 8 : 0);
 }
 
 template <int B, int BITS, bool AFF>
-__global__ __launch_bounds__(QT) void column_block_kernel(ColArgs a) {
+__global__ __launch_bounds__(QT) void column_block_kernel(ColArgs a, const float* __restrict__ ud,
+                                                          const float* __restrict__ urinv) {
+  // ud: this block's B x B piece of U (entries left of the diagonal and outside the
+  // matrix are zero), urinv: 1 / U_jj (zero outside the matrix).
   constexpr int K = 1 << BITS;
+  constexpr int NSB = B / SB;
+  constexpr int LD = B + 1;                  // odd: row-per-lane and tile accesses are conflict-free
   extern __shared__ __align__(16) float smq[];
-  float* sU = smq;            // [B][B], zero outside the stored upper triangle / the block
-  float* sRinv = smq + B * B; // [B]  1 / U_jj
+  float* sUd = smq;                          // [NSB][32][32] diagonal sub-blocks of the U block
+  float* sRinv = sUd + NSB * SB * SB;        // [B]
+  float* sWall = sRinv + B;                  // [4 wavefronts][64][LD]
 
-  const int tid = threadIdx.x;
-  const int64_t row = (int64_t)blockIdx.x * QT + tid;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ml = lane & 31, hl = lane >> 5;
+  float* sW = sWall + wave * 64 * LD;
+  const int64_t row0 = (int64_t)blockIdx.x * QT + wave * 64;   // first row of this wavefront
+  const int64_t row = row0 + lane;
   const bool valid = row < a.r;
   const int nb = a.nb;
 
-  for (int f = tid; f < B * B; f += QT) {
-    int j = f / B, jj = f - j * B;
-    float v = 0.0f;
-    if (j < nb && jj < nb && jj >= j) v = a.U[(a.i0 + j) * a.ldu + a.i0 + jj];
-    sU[f] = v;
+  for (int f = tid; f < NSB * SB * SB; f += QT) {
+    int s = f / (SB * SB), j = (f / SB) % SB, jj = f % SB;
+    sUd[f] = ud[(s * SB + j) * B + s * SB + jj];
   }
-  for (int j = tid; j < B; j += QT) sRinv[j] = (j < nb) ? 1.0f / a.U[(a.i0 + j) * a.ldu + a.i0 + j] : 0.0f;
+  for (int j = tid; j < B; j += QT) sRinv[j] = urinv[j];
 
-  float w[B];
-  const float* wrow = a.W + (valid ? row : 0) * a.ldw + a.i0;
+  // this wavefront's 64 x B piece of W -> LDS (rows past r and columns past c read as zero)
   if (a.vecw && nb == B) {
-#pragma unroll
-    for (int q4 = 0; q4 < B / 4; ++q4) {
-      float4 v = valid ? *reinterpret_cast<const float4*>(wrow + 4 * q4) : make_float4(0.f, 0.f, 0.f, 0.f);
-      w[4 * q4 + 0] = v.x; w[4 * q4 + 1] = v.y; w[4 * q4 + 2] = v.z; w[4 * q4 + 3] = v.w;
+    for (int f = lane; f < 64 * (B / 4); f += 64) {
+      int rr = f / (B / 4), c4 = f % (B / 4);
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (row0 + rr < a.r) v = *reinterpret_cast<const float4*>(a.W + (row0 + rr) * a.ldw + a.i0 + 4 * c4);
+      float* d = sW + rr * LD + 4 * c4;
+      d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
     }
   } else {
-#pragma unroll
-    for (int j = 0; j < B; ++j) w[j] = (valid && j < nb) ? wrow[j] : 0.0f;
+    for (int f = lane; f < 64 * B; f += 64) {
+      int rr = f / B, cc = f % B;
+      sW[rr * LD + cc] = (row0 + rr < a.r && cc < nb) ? a.W[(row0 + rr) * a.ldw + a.i0 + cc] : 0.0f;
+    }
   }
 
-  float g[K], mid[K - 1];
+  typename GridVec<K>::type g, mid;
   float S = 1.0f, Z = 0.0f, invS = 1.0f;
-  if (!AFF) {
 #pragma unroll
-    for (int m = 0; m < K; ++m) g[m] = valid ? a.grid[row * K + m] : 0.0f;
+  for (int m = 0; m < K; ++m) g[m] = (!AFF && valid) ? a.grid[row * K + m] : 0.0f;
 #pragma unroll
-    for (int m = 0; m < K - 1; ++m) mid[m] = 0.5f * (g[m] + g[m + 1]);
-  }
+  for (int m = 0; m < K; ++m) mid[m] = (m < K - 1) ? 0.5f * (g[m] + g[m < K - 1 ? m + 1 : m]) : 0.0f;
   __syncthreads();
 
-  uint32_t pk[B / 4];
-#pragma unroll
-  for (int q4 = 0; q4 < B / 4; ++q4) pk[q4] = 0u;
   float loss = 0.0f;
   const float qmax = (float)(K - 1);
 
+  for (int sb = 0; sb < NSB; ++sb) {
+    const int cb = sb * SB;                       // first column of the sub-block within the block
+    float ws[SB], e[SB];
 #pragma unroll
-  for (int j = 0; j < B; ++j) {
-    if (j < nb) {
+    for (int k = 0; k < SB; ++k) ws[k] = sW[lane * LD + cb + k];
+    const float* su = sUd + sb * SB * SB;
+    uint32_t pk[SB / 4];
+#pragma unroll
+    for (int q4 = 0; q4 < SB / 4; ++q4) pk[q4] = 0u;
+
+    // Columns past the end of a ragged last block hold zeros and have 1 / U_jj = 0, so
+    // they produce E = 0 and change nothing; only the stores are guarded.
+#pragma unroll
+    for (int j = 0; j < SB; ++j) {
       float q;
       int code;
-      const float wj = w[j];
+      const float wj = ws[j];
       if (AFF) {
-        const int64_t col = a.i0 + j;
+        const int64_t col = a.i0 + cb + j;
         if (j == 0 || (col % a.group) == 0) {
-          const float* sz = a.grid + ((valid ? row : 0) * a.ngroups + col / a.group) * 2;
+          const int64_t gi = (col < a.c ? col : a.c - 1) / a.group;
+          const float* sz = a.grid + ((valid ? row : 0) * a.ngroups + gi) * 2;
           S = sz[0];
           Z = sz[1];
           invS = 1.0f / S;
@@ -109,47 +163,98 @@ __global__ __launch_bounds__(QT) void column_block_kernel(ColArgs a) {
         code = (int)wi;
         q = (wi - Z) * S;
       } else {
-        quant_nu<K>(wj, g, mid, q, code);
+        quant_nu_vec(wj, g, mid, q, code);
       }
-      const float e = (wj - q) * sRinv[j];
-      w[j] = q;
+      const float ej = (wj - q) * sRinv[cb + j];
+      e[j] = ej;
+      ws[j] = q;
       pk[j >> 2] |= (uint32_t)code << (8 * (j & 3));
-      loss = fmaf(0.5f * e, e, loss);
-      if (valid) a.Et[(int64_t)j * a.rpad + row] = e;
-      const float* urow = sU + j * B;
+      loss = fmaf(0.5f * ej, ej, loss);
+      a.Et[(int64_t)(cb + j) * a.rpad + row] = ej;      // rpad covers every lane of the launch
 #pragma unroll
-      for (int jj = j + 1; jj < B; ++jj) w[jj] = fmaf(-e, urow[jj], w[jj]);
+      for (int jj = j + 1; jj < SB; ++jj) ws[jj] = fmaf(-ej, su[j * SB + jj], ws[jj]);
+    }
+
+    // quantized values back to the LDS piece, codes to global memory
+#pragma unroll
+    for (int k = 0; k < SB; ++k) sW[lane * LD + cb + k] = ws[k];
+    if (valid) {
+      uint8_t* cout = a.codes + row * a.c + a.i0 + cb;
+      if (cb + SB <= nb && ((a.c | a.i0) % 4) == 0) {
+#pragma unroll
+        for (int q4 = 0; q4 < SB / 4; ++q4) reinterpret_cast<uint32_t*>(cout)[q4] = pk[q4];
+      } else {
+#pragma unroll
+        for (int j = 0; j < SB; ++j)
+          if (cb + j < nb) cout[j] = (uint8_t)((pk[j >> 2] >> (8 * (j & 3))) & 0xffu);
+      }
+    }
+
+    if (sb + 1 < NSB) {
+      // A operands of the 64 x 32 error block for the two 32-row halves: lanes 0..31 supply
+      // k even, lanes 32..63 k odd, of rows (lane % 32) and (lane % 32) + 32.
+      float a_lo[SB / 2], a_hi[SB / 2];
+#pragma unroll
+      for (int kk = 0; kk < SB / 2; ++kk) {
+        const float x = -e[2 * kk], y = -e[2 * kk + 1];
+        const float xs = __shfl_xor(x, 32, 64), ys = __shfl_xor(y, 32, 64);
+        a_lo[kk] = hl ? ys : x;     // rows 0..31:  lane < 32 -> own x;  lane >= 32 -> y of lane - 32
+        a_hi[kk] = hl ? y : xs;     // rows 32..63: lane < 32 -> x of lane + 32;  lane >= 32 -> own y
+      }
+      for (int t = sb + 1; t < NSB; ++t) {
+        float b[SB / 2];
+#pragma unroll
+        for (int kk = 0; kk < SB / 2; ++kk) b[kk] = ud[(cb + 2 * kk + hl) * B + t * SB + ml];
+        floatx16 c_lo, c_hi;
+        float* tl = sW + t * SB + ml;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = 8 * (v >> 2) + 4 * hl + (v & 3);
+          c_lo[v] = tl[m * LD];
+          c_hi[v] = tl[(m + 32) * LD];
+        }
+#pragma unroll
+        for (int kk = 0; kk < SB / 2; ++kk) {
+          c_lo = __builtin_amdgcn_mfma_f32_32x32x2f32(a_lo[kk], b[kk], c_lo, 0, 0, 0);
+          c_hi = __builtin_amdgcn_mfma_f32_32x32x2f32(a_hi[kk], b[kk], c_hi, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = 8 * (v >> 2) + 4 * hl + (v & 3);
+          tl[m * LD] = c_lo[v];
+          tl[(m + 32) * LD] = c_hi[v];
+        }
+      }
     }
   }
 
-  if (valid) {
-    float* wout = a.W + row * a.ldw + a.i0;
-    uint8_t* cout = a.codes + row * a.c + a.i0;
-    if (a.vecw && nb == B) {
-#pragma unroll
-      for (int q4 = 0; q4 < B / 4; ++q4)
-        *reinterpret_cast<float4*>(wout + 4 * q4) =
-            make_float4(w[4 * q4], w[4 * q4 + 1], w[4 * q4 + 2], w[4 * q4 + 3]);
-    } else {
-#pragma unroll
-      for (int j = 0; j < B; ++j)
-        if (j < nb) wout[j] = w[j];
+  // W_hat of the block back to global memory, row by row (coalesced)
+  if (a.vecw && nb == B) {
+    for (int f = lane; f < 64 * (B / 4); f += 64) {
+      int rr = f / (B / 4), c4 = f % (B / 4);
+      if (row0 + rr < a.r) {
+        const float* d = sW + rr * LD + 4 * c4;
+        *reinterpret_cast<float4*>(a.W + (row0 + rr) * a.ldw + a.i0 + 4 * c4) = make_float4(d[0], d[1], d[2], d[3]);
+      }
     }
-    if (nb == B && ((a.c | a.i0) % 4) == 0) {
-#pragma unroll
-      for (int q4 = 0; q4 < B / 4; ++q4) reinterpret_cast<uint32_t*>(cout)[q4] = pk[q4];
-    } else {
-#pragma unroll
-      for (int j = 0; j < B; ++j)
-        if (j < nb) cout[j] = (uint8_t)((pk[j >> 2] >> (8 * (j & 3))) & 0xffu);
+  } else {
+    for (int f = lane; f < 64 * B; f += 64) {
+      int rr = f / B, cc = f % B;
+      if (row0 + rr < a.r && cc < nb) a.W[(row0 + rr) * a.ldw + a.i0 + cc] = sW[rr * LD + cc];
     }
-    if (a.row_loss) a.row_loss[row] = (a.first ? 0.0f : a.row_loss[row]) + loss;
   }
+  if (valid && a.row_loss) a.row_loss[row] = (a.first ? 0.0f : a.row_loss[row]) + loss;
 }
 
 template <int B>
-lq_status launch_column(const ColArgs& a, const lq_params* P, hipStream_t st) {
-  const size_t lds = (size_t)(B * B + B) * sizeof(float);
+constexpr size_t column_lds_bytes() {
+  return (size_t)((B / SB) * SB * SB + B + 4 * 64 * (B + 1)) * sizeof(float);
+}
+
+template <int B>
+lq_status launch_column(const ColArgs& a, const float* ud, const float* urinv, const lq_params* P,
+                        hipStream_t st) {
+  const size_t lds = column_lds_bytes<B>();
   dim3 grid((unsigned)lq::ceil_div(a.r, QT)), block(QT);
 #define LQ_COL(BITS, AFF)                                                                          \
   do {                                                                                             \
@@ -159,7 +264,7 @@ lq_status launch_column(const ColArgs& a, const lq_params* P, hipStream_t st) {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));     \
       done = true;                                                                                 \
     }                                                                                              \
-    hipLaunchKernelGGL((column_block_kernel<B, BITS, AFF>), grid, block, lds, st, a);              \
+    hipLaunchKernelGGL((column_block_kernel<B, BITS, AFF>), grid, block, lds, st, a, ud, urinv);   \
   } while (0)
   const bool aff = P->mode == LQ_GRID_AFFINE;
   if (P->bits == 2) { if (aff) LQ_COL(2, true); else LQ_COL(2, false); }
@@ -170,9 +275,11 @@ lq_status launch_column(const ColArgs& a, const lq_params* P, hipStream_t st) {
   return LQ_OK;
 }
 
-
-lq_status launch_column_128(const ColArgs& a, const lq_params* P, hipStream_t st);
-lq_status launch_column_64(const ColArgs& a, const lq_params* P, hipStream_t st);
-lq_status launch_column_32(const ColArgs& a, const lq_params* P, hipStream_t st);
+lq_status launch_column_128(const ColArgs& a, const float* ud, const float* urinv,
+                            const lq_params* P, hipStream_t st);
+lq_status launch_column_64(const ColArgs& a, const float* ud, const float* urinv,
+                            const lq_params* P, hipStream_t st);
+lq_status launch_column_32(const ColArgs& a, const float* ud, const float* urinv,
+                            const lq_params* P, hipStream_t st);
 
 }  // namespace lq

@@ -42,10 +42,19 @@ __device__ __forceinline__ void decode_upper(int idx, int T, int& bi, int& bj) {
   bj = r + (idx - (r * T - (r * (r - 1)) / 2));
 }
 
-template <int KT, bool VEC>
+// Load one k-chunk (KT rows x 128 columns) of an operand into registers.  FAST: the
+// whole chunk is inside the matrix and 16-byte aligned, no predicates.  Otherwise rows
+// past kend and columns past ncols read as zero, element by element if need be.
+template <int KT, bool VEC, bool FAST>
 __device__ __forceinline__ void tn_load_chunk(const float* __restrict__ base, int64_t ld, int64_t k0,
                                               int64_t kend, int64_t col0, int64_t ncols,
                                               float4 (&r)[KT / 8], int tid) {
+  if (FAST) {
+    const float* src = base + (k0 + (tid >> 5)) * ld + col0 + 4 * (tid & 31);
+#pragma unroll
+    for (int p = 0; p < KT / 8; ++p) r[p] = *reinterpret_cast<const float4*>(src + (int64_t)(8 * p) * ld);
+    return;
+  }
 #pragma unroll
   for (int p = 0; p < KT / 8; ++p) {
     int f = tid + p * WG_THREADS;
@@ -77,8 +86,8 @@ __device__ __forceinline__ void tn_store_chunk(float* __restrict__ s, const floa
   }
 }
 
-template <int KT, bool SYM, bool PARTIAL, bool VEC>
-__global__ __launch_bounds__(WG_THREADS, 2) void tn_gemm_kernel(TnGemmArgs a) {
+template <int KT, bool SYM, bool PARTIAL, bool VEC, int MINW = 2>
+__global__ __launch_bounds__(WG_THREADS, MINW) void tn_gemm_kernel(TnGemmArgs a) {
   extern __shared__ __align__(16) float smem[];
   constexpr int STAGE = KT * TILE;   // floats per operand per buffer; P buffers, then Q buffers
 
@@ -106,18 +115,25 @@ __global__ __launch_bounds__(WG_THREADS, 2) void tn_gemm_kernel(TnGemmArgs a) {
 
   if (kbeg < kend) {
     float4 rp[KT / 8], rq[KT / 8];
-    tn_load_chunk<KT, VEC>(a.P, a.ldp, kbeg, kend, m0, a.M, rp, tid);
-    if (!diag) tn_load_chunk<KT, VEC>(a.Q, a.ldq, kbeg, kend, n0, a.N, rq, tid);
+    // interior tiles of an aligned operand take the predicate-free loads for every full chunk
+    const bool inner = VEC && (m0 + TILE <= a.M) && (n0 + TILE <= a.N);
+    auto load = [&](int64_t k0) {
+      if (inner && k0 + KT <= kend) {
+        tn_load_chunk<KT, VEC, true>(a.P, a.ldp, k0, kend, m0, a.M, rp, tid);
+        if (!diag) tn_load_chunk<KT, VEC, true>(a.Q, a.ldq, k0, kend, n0, a.N, rq, tid);
+      } else {
+        tn_load_chunk<KT, VEC, false>(a.P, a.ldp, k0, kend, m0, a.M, rp, tid);
+        if (!diag) tn_load_chunk<KT, VEC, false>(a.Q, a.ldq, k0, kend, n0, a.N, rq, tid);
+      }
+    };
+    load(kbeg);
     tn_store_chunk<KT>(smem, rp, tid);
     if (!diag) tn_store_chunk<KT>(smem + 2 * STAGE, rq, tid);
     __syncthreads();
     int buf = 0;
     for (int64_t k0 = kbeg; k0 < kend; k0 += KT) {
       const bool more = (k0 + KT) < kend;
-      if (more) {
-        tn_load_chunk<KT, VEC>(a.P, a.ldp, k0 + KT, kend, m0, a.M, rp, tid);
-        if (!diag) tn_load_chunk<KT, VEC>(a.Q, a.ldq, k0 + KT, kend, n0, a.N, rq, tid);
-      }
+      if (more) load(k0 + KT);
       const float* cp = smem + buf * STAGE;
       mma_chunk_kmajor<KT>(cp, diag ? cp : cp + 2 * STAGE, wm, wn, lane, acc);
       if (more) {

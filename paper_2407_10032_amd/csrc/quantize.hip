@@ -5,8 +5,8 @@
 //   * the column kernel: one lane owns one row and keeps that row's B weights of the
 //     block in registers; for every column it quantizes against the row's grid
 //     (line 13 / 15), forms E = (w - q) / U_jj (line 16) and subtracts E * U[j, j+1:]
-//     from its remaining registers (line 17).  The B x B block of U is read from LDS at
-//     wave-uniform addresses.  E is written transposed ([B x r]) so that
+//     from its remaining registers (line 17).  The B x B diagonal blocks of U are packed
+//     once per layer and read as wave-uniform scalars.  E is written transposed so that
 //   * the trailing update W[:, i+B:] -= E U[i:i+B, i+B:] (line 19) is a k-major
 //     fp32 MFMA product of the same kind as the Hessian accumulation.
 #include "lq_common.h"
@@ -18,12 +18,43 @@ namespace {
 
 constexpr int KT = 32;
 
+// Pack the diagonal B x B blocks of U: ud[blk][j][jj] = U[i0+j][i0+jj] for jj >= j inside the
+// matrix, zero elsewhere; urinv[blk][j] = 1 / U[i0+j][i0+j] (0 outside the matrix).
+__global__ __launch_bounds__(256) void pack_diag_blocks_kernel(const float* __restrict__ U, int64_t ldu,
+                                                               int64_t c, int B, float* __restrict__ ud,
+                                                               float* __restrict__ urinv) {
+  const int64_t i0 = (int64_t)blockIdx.x * B;
+  float* dst = ud + (int64_t)blockIdx.x * B * B;
+  for (int f = threadIdx.x; f < B * B; f += 256) {
+    int j = f / B, jj = f - j * B;
+    float v = 0.0f;
+    if (jj >= j && i0 + jj < c) v = U[(i0 + j) * ldu + i0 + jj];
+    dst[f] = v;
+  }
+  for (int j = threadIdx.x; j < B; j += 256)
+    urinv[(int64_t)blockIdx.x * B + j] = (i0 + j < c) ? 1.0f / U[(i0 + j) * ldu + i0 + j] : 0.0f;
+}
+
+struct QuantPlan {
+  int64_t rpad, nblk;
+  size_t off_ud, off_rinv, total;
+};
+
+QuantPlan make_plan(int64_t r, int64_t c, int B) {
+  QuantPlan p;
+  p.rpad = lq::ceil_div(r > 0 ? r : 1, lq::QT) * lq::QT;   // one slot per lane of the column kernel
+  p.nblk = lq::ceil_div(c, B);
+  p.off_ud = lq::align_up((size_t)p.rpad * B * sizeof(float), 256);
+  p.off_rinv = p.off_ud + lq::align_up((size_t)p.nblk * B * B * sizeof(float), 256);
+  p.total = p.off_rinv + lq::align_up((size_t)p.nblk * B * sizeof(float), 256);
+  return p;
+}
+
 }  // namespace
 
 namespace lq {
-size_t quantize_workspace_bytes(int64_t r, int block) {
-  int64_t rpad = ceil_div(r > 0 ? r : 1, 64) * 64;
-  return (size_t)rpad * (size_t)(block > 0 ? block : 128) * sizeof(float);
+size_t quantize_workspace_bytes(int64_t r, int64_t c, int block) {
+  return make_plan(r, c, block > 0 ? block : 128).total;
 }
 }  // namespace lq
 
@@ -39,16 +70,18 @@ extern "C" lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t l
   const int B = P->block;
   if (B != 32 && B != 64 && B != 128)
     return lq::fail(LQ_ERR_UNSUPPORTED, "lq_quantize_layer: block=%d (supported: 32, 64, 128)", B);
-  size_t need = lq::quantize_workspace_bytes(r, B);
+  const QuantPlan plan = make_plan(r, c, B);
+  size_t need = plan.total;
   if (!ws || !lq::aligned(ws, 256) || ws_bytes < need)
     return lq::fail(LQ_ERR_WORKSPACE, "lq_quantize_layer: workspace needs %zu bytes, 256-byte aligned", need);
   if (r == 0) return LQ_OK;
 
   hipStream_t st = (hipStream_t)stream;
-  const int64_t rpad = lq::ceil_div(r, 64) * 64;
+  const int64_t rpad = plan.rpad;
+  float* ud = (float*)((char*)ws + plan.off_ud);
+  float* urinv = (float*)((char*)ws + plan.off_rinv);
   lq::ColArgs a;
   a.W = W; a.ldw = ldw; a.r = r; a.c = c;
-  a.U = U; a.ldu = ldu;
   a.grid = grid;
   a.group = (P->mode == LQ_GRID_AFFINE) ? (P->group_size > 0 ? P->group_size : (int)c) : (int)c;
   a.ngroups = (int)(c / a.group);
@@ -67,13 +100,19 @@ extern "C" lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t l
     attr_done = true;
   }
 
+  hipLaunchKernelGGL(pack_diag_blocks_kernel, dim3((unsigned)plan.nblk), dim3(256), 0, st, U, ldu, c, B,
+                     ud, urinv);
+  LQ_CHECK_LAUNCH("pack_diag_blocks_kernel");
+
   for (int64_t i0 = 0; i0 < c; i0 += B) {
+    const float* udb = ud + (i0 / B) * B * B;
+    const float* rib = urinv + (i0 / B) * B;
     a.i0 = i0;
     a.nb = (int)((c - i0) < B ? (c - i0) : B);
     a.first = (i0 == 0);
-    lq_status s2 = (B == 128) ? lq::launch_column_128(a, P, st)
-                 : (B == 64)  ? lq::launch_column_64(a, P, st)
-                              : lq::launch_column_32(a, P, st);
+    lq_status s2 = (B == 128) ? lq::launch_column_128(a, udb, rib, P, st)
+                 : (B == 64)  ? lq::launch_column_64(a, udb, rib, P, st)
+                              : lq::launch_column_32(a, udb, rib, P, st);
     if (s2 != LQ_OK) return s2;
     const int64_t rest = c - i0 - a.nb;
     if (rest > 0) {
