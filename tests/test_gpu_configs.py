@@ -5,8 +5,9 @@ the bench (all 262144 tokens resident, one lq_hessian_accumulate call), against 
 oracle computed end to end from the same inputs; grids, codes and loss are compared on a
 seeded sample of rows, which is exact because rows are independent problems (Eq. 1).
 Configurations 3-5 keep their real column count and structure; the token count (the
-reduction length of the Gram product only) and, for the 405B-shaped layer, the row count are
-reduced so that the float64 oracle finishes in about a minute.  Bars: codes >= 99.9 %,
+reduction length of the Gram product) is cut to a quarter or half and the row count of the
+two largest layers is reduced, so that the float64 oracle finishes in about a minute each.
+Fewer tokens make H worse conditioned than in the real layer, i.e. the test is harder.  Bars: codes >= 99.9 %,
 grids within 1e-4 relative, sampled-row layer loss within 1e-3 relative.
 """
 import time
@@ -70,14 +71,20 @@ def _check_hud(Hg, Ug, dg, H, U, d, n_tokens):
 
 
 def _compare_rows(cfg, P, W_rows, H, ref, grid_g, What_g, codes_g):
-    agree = hx.code_agreement(codes_g, ref["codes"])
+    """Grid match per row, code agreement over the rows whose grid matches (a different but
+    equally good grid legitimately gives other codes), loss ratio over all sampled rows."""
+    if cfg.mode == "nu":
+        row_ok = hx.nu_grid_match(grid_g, ref["grid"])
+        gok = row_ok.mean()
+    else:
+        m = hx.aff_grid_match(grid_g, ref["grid"])
+        row_ok = m.all(axis=1)
+        gok = m.mean()
+    agree = hx.code_agreement(codes_g[row_ok], ref["codes"][row_ok]) if row_ok.any() else 0.0
     l_gpu = orc.layer_loss(W_rows, What_g, H)
     l_ref = orc.layer_loss(W_rows, ref["W_hat"], H)
-    if cfg.mode == "nu":
-        gok = hx.nu_grid_match(grid_g, ref["grid"]).mean()
-    else:
-        gok = hx.aff_grid_match(grid_g, ref["grid"]).mean()
-    _say(f"    grids matching {gok:.4f}, codes equal {agree:.5f}, loss gpu/ref {l_gpu / l_ref:.6f}")
+    _say(f"    grids matching {gok:.4f} ({int(row_ok.sum())}/{row_ok.size} rows entirely), codes equal on those "
+         f"rows {agree:.5f}, loss gpu/ref {l_gpu / l_ref:.6f}")
     return gok, agree, l_gpu / l_ref
 
 
@@ -108,9 +115,9 @@ def test_config2_full_size():
 
 
 def test_config3_shape_nonuniform_3bit():
-    cfg = lq_synth.CONFIGS["c3"].scaled(n_tokens=16384)
+    cfg = lq_synth.CONFIGS["c3"].scaled(n_tokens=65536)
     P = hx.params_for(cfg)
-    _say("c3 (c = 11008, silu-product activations, 3-bit non-uniform), 16384 tokens")
+    _say("c3 (c = 11008, silu-product activations, 3-bit non-uniform), 65536 tokens")
     Hg, Ug, dg, grid, Wq, codes, _ = _device_layer(cfg, P)
     H = _oracle_hessian(cfg)
     U, d = orc.cholesky_inv(H, cfg.damp)
@@ -125,9 +132,9 @@ def test_config3_shape_nonuniform_3bit():
 
 
 def test_config4_shape_affine_group128():
-    cfg = lq_synth.CONFIGS["c4"].scaled(n_tokens=16384, r=4096)
+    cfg = lq_synth.CONFIGS["c4"].scaled(n_tokens=32768, r=4096)
     P = hx.params_for(cfg)
-    _say("c4 (c = 8192, 4-bit affine, group 128, T = 2048), 16384 tokens, 4096 rows on the device")
+    _say("c4 (c = 8192, 4-bit affine, group 128, T = 2048), 32768 tokens, 4096 rows on the device")
     Hg, Ug, dg, grid, Wq, codes, _ = _device_layer(cfg, P)
     H = _oracle_hessian(cfg)
     U, d = orc.cholesky_inv(H, cfg.damp)
@@ -140,12 +147,12 @@ def test_config4_shape_affine_group128():
     What, codes_ref, _ = orc.quantize_layer(W_rows, U, SZ, "aff", cfg.bits, group_size=cfg.group_size, B=cfg.block)
     gok, agree, lr = _compare_rows(cfg, P, W_rows, H, dict(grid=SZ, W_hat=What, codes=codes_ref),
                                    grid.cpu().numpy()[rows], Wq.cpu().numpy()[rows], codes.cpu().numpy()[rows])
-    assert gok >= 0.95 and agree >= 0.995 and abs(lr - 1.0) < 2e-3
+    assert gok >= 0.95 and agree >= 0.999 and abs(lr - 1.0) < 2e-3
 
 
 def test_config5_shape_both_modes():
-    base = lq_synth.CONFIGS["c5"].scaled(n_tokens=20480, r=2048)
-    _say("c5 (c = 16384), 20480 tokens, 2048 rows on the device: Gram, inverse, Cholesky")
+    base = lq_synth.CONFIGS["c5"].scaled(n_tokens=32768, r=2048)
+    _say("c5 (c = 16384), 32768 tokens, 2048 rows on the device: Gram, inverse, Cholesky")
     # 3-bit non-uniform run on the layer
     cfg = base.scaled(mode="nu", bits=3, group_size=0)
     P = hx.params_for(cfg)
@@ -188,10 +195,10 @@ def test_config5_shape_both_modes():
     Pb = hx.params_for(cfa, T=256)
     gridb = hx.gpu_fit_grid(Wd, dg, Pb)
     Wq, codes, _ = hx.gpu_quantize(Wd, Ug, gridb, Pb)
-    rb = rows[:3]
+    rb = rows[:6]
     W_rows = lq_synth.weights(cfa, rb)
     SZ = orc.fit_grid_aff(W_rows, d, 2, cfa.p, group_size=64, T=256)
     What, codes_ref, _ = orc.quantize_layer(W_rows, U, SZ, "aff", 2, group_size=64, B=cfa.block)
     gok, agree, lr = _compare_rows(cfa, Pb, W_rows, H, dict(grid=SZ, W_hat=What, codes=codes_ref),
                                    gridb.cpu().numpy()[rb], Wq.cpu().numpy()[rb], codes.cpu().numpy()[rb])
-    assert gok >= 0.95 and agree >= 0.995 and abs(lr - 1.0) < 2e-3
+    assert gok >= 0.99 and agree >= 0.999 and abs(lr - 1.0) < 2e-3
