@@ -49,7 +49,8 @@ __device__ __forceinline__ void mma_chunk_kmajor(const float* __restrict__ sP,
   const int kl = lane >> 5, ml = lane & 31;
   const float* p = sP + kl * TILE + wm * 64 + ml;   // + 2*kk*TILE per step: immediate offsets
   const float* q = sQ + kl * TILE + wn * 64 + ml;
-  // operands of step kk+1 are read while the MFMAs of step kk run
+  // operands of step kk+1 are read while the MFMAs of step kk run; the scheduling
+  // barriers keep the compiler from sinking the reads below the MFMAs again
   float a0[2], a1[2], b0[2], b1[2];
   a0[0] = p[0]; a1[0] = p[32]; b0[0] = q[0]; b1[0] = q[32];
 #pragma unroll
@@ -61,10 +62,12 @@ __device__ __forceinline__ void mma_chunk_kmajor(const float* __restrict__ sP,
       b0[nxt] = q[2 * (kk + 1) * TILE];
       b1[nxt] = q[2 * (kk + 1) * TILE + 32];
     }
+    __builtin_amdgcn_sched_barrier(0);
     acc.t[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[cur], b0[cur], acc.t[0][0], 0, 0, 0);
     acc.t[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[cur], b1[cur], acc.t[0][1], 0, 0, 0);
     acc.t[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[cur], b0[cur], acc.t[1][0], 0, 0, 0);
     acc.t[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[cur], b1[cur], acc.t[1][1], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 

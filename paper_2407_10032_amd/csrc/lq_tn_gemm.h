@@ -42,54 +42,107 @@ __device__ __forceinline__ void decode_upper(int idx, int T, int& bi, int& bj) {
   bj = r + (idx - (r * T - (r * (r - 1)) / 2));
 }
 
-// Load one k-chunk (KT rows x 128 columns) of an operand into registers.  FAST: the
-// whole chunk is inside the matrix and 16-byte aligned, no predicates.  Otherwise rows
-// past kend and columns past ncols read as zero, element by element if need be.
-template <int KT, bool VEC, bool FAST>
-__device__ __forceinline__ void tn_load_chunk(const float* __restrict__ base, int64_t ld, int64_t k0,
-                                              int64_t kend, int64_t col0, int64_t ncols,
-                                              float4 (&r)[KT / 8], int tid) {
-  if (FAST) {
-    const float* src = base + (k0 + (tid >> 5)) * ld + col0 + 4 * (tid & 31);
-#pragma unroll
-    for (int p = 0; p < KT / 8; ++p) r[p] = *reinterpret_cast<const float4*>(src + (int64_t)(8 * p) * ld);
-    return;
-  }
-#pragma unroll
-  for (int p = 0; p < KT / 8; ++p) {
-    int f = tid + p * WG_THREADS;
-    int64_t k = k0 + (f >> 5);
-    int64_t col = col0 + 4 * (f & 31);
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (k < kend) {
-      const float* src = base + k * ld + col;
-      if (VEC && col + 3 < ncols) {
-        v = *reinterpret_cast<const float4*>(src);
-      } else {
-        if (col + 0 < ncols) v.x = src[0];
-        if (col + 1 < ncols) v.y = src[1];
-        if (col + 2 < ncols) v.z = src[2];
-        if (col + 3 < ncols) v.w = src[3];
-      }
+// One k-chunk (KT rows x 128 columns) of an operand in registers: KT / 8 float4 per thread,
+// held as named members so that they stay in registers.
+template <int KT> struct ChunkRegs;
+template <> struct ChunkRegs<16> { float4 r0, r1; };
+template <> struct ChunkRegs<32> { float4 r0, r1, r2, r3; };
+
+// Element-wise guarded load of one float4 (rows past kend / columns past ncols read zero).
+template <bool VEC>
+__device__ __forceinline__ float4 tn_load_guarded(const float* __restrict__ base, int64_t ld,
+                                                  int64_t k, int64_t kend, int64_t col,
+                                                  int64_t ncols) {
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (k < kend) {
+    const float* src = base + k * ld + col;
+    if (VEC && col + 3 < ncols) {
+      v = *reinterpret_cast<const float4*>(src);
+    } else {
+      if (col + 0 < ncols) v.x = src[0];
+      if (col + 1 < ncols) v.y = src[1];
+      if (col + 2 < ncols) v.z = src[2];
+      if (col + 3 < ncols) v.w = src[3];
     }
-    r[p] = v;
   }
+  return v;
+}
+
+// FAST: the whole chunk is inside the matrix and 16-byte aligned: no predicates, a
+// wave-uniform row base (scalar registers) plus a 32-bit per-thread offset.
+template <int KT, bool VEC, bool FAST>
+__device__ __forceinline__ ChunkRegs<KT> tn_load_chunk(const float* __restrict__ base, int64_t ld,
+                                                       int64_t k0, int64_t kend, int64_t col0,
+                                                       int64_t ncols, int tid) {
+  ChunkRegs<KT> c;
+  if (FAST) {
+    const float* rowbase = base + k0 * ld + col0;
+    const int off = (tid >> 5) * (int)ld + 4 * (tid & 31);
+    c.r0 = *reinterpret_cast<const float4*>(rowbase + off);
+    c.r1 = *reinterpret_cast<const float4*>(rowbase + (off + 8 * (int)ld));
+    if constexpr (KT == 32) {
+      c.r2 = *reinterpret_cast<const float4*>(rowbase + (off + 16 * (int)ld));
+      c.r3 = *reinterpret_cast<const float4*>(rowbase + (off + 24 * (int)ld));
+    }
+  } else {
+    const int64_t k = k0 + (tid >> 5);
+    const int64_t col = col0 + 4 * (tid & 31);
+    c.r0 = tn_load_guarded<VEC>(base, ld, k, kend, col, ncols);
+    c.r1 = tn_load_guarded<VEC>(base, ld, k + 8, kend, col, ncols);
+    if constexpr (KT == 32) {
+      c.r2 = tn_load_guarded<VEC>(base, ld, k + 16, kend, col, ncols);
+      c.r3 = tn_load_guarded<VEC>(base, ld, k + 24, kend, col, ncols);
+    }
+  }
+  return c;
 }
 
 template <int KT>
-__device__ __forceinline__ void tn_store_chunk(float* __restrict__ s, const float4 (&r)[KT / 8],
-                                               int tid) {
-#pragma unroll
-  for (int p = 0; p < KT / 8; ++p) {
-    int f = tid + p * WG_THREADS;
-    *reinterpret_cast<float4*>(s + (f >> 5) * TILE + 4 * (f & 31)) = r[p];
+__device__ __forceinline__ void tn_store_chunk(float* __restrict__ s, const ChunkRegs<KT>& c, int tid) {
+  float* d = s + (tid >> 5) * TILE + 4 * (tid & 31);
+  *reinterpret_cast<float4*>(d) = c.r0;
+  *reinterpret_cast<float4*>(d + 8 * TILE) = c.r1;
+  if constexpr (KT == 32) {
+    *reinterpret_cast<float4*>(d + 16 * TILE) = c.r2;
+    *reinterpret_cast<float4*>(d + 24 * TILE) = c.r3;
+  }
+}
+
+// The k loop of one tile: global loads of stage s+1 are issued before the MFMAs of stage s
+// and stored to the other LDS buffer after them.
+template <int KT, bool VEC, bool FAST>
+__device__ __forceinline__ void tn_mainloop(const TnGemmArgs& a, float* smem, int64_t kbeg,
+                                            int64_t kend, int64_t m0, int64_t n0, bool diag, int wm,
+                                            int wn, int lane, int tid, Acc2x2& acc) {
+  constexpr int STAGE = KT * TILE;
+  ChunkRegs<KT> rp = tn_load_chunk<KT, VEC, FAST>(a.P, a.ldp, kbeg, kend, m0, a.M, tid);
+  ChunkRegs<KT> rq = rp;
+  if (!diag) rq = tn_load_chunk<KT, VEC, FAST>(a.Q, a.ldq, kbeg, kend, n0, a.N, tid);
+  tn_store_chunk<KT>(smem, rp, tid);
+  if (!diag) tn_store_chunk<KT>(smem + 2 * STAGE, rq, tid);
+  __syncthreads();
+  int buf = 0;
+  for (int64_t k0 = kbeg; k0 < kend; k0 += KT) {
+    const bool more = (k0 + KT) < kend;
+    if (more) {
+      rp = tn_load_chunk<KT, VEC, FAST>(a.P, a.ldp, k0 + KT, kend, m0, a.M, tid);
+      if (!diag) rq = tn_load_chunk<KT, VEC, FAST>(a.Q, a.ldq, k0 + KT, kend, n0, a.N, tid);
+    }
+    const float* cp = smem + buf * STAGE;
+    mma_chunk_kmajor<KT>(cp, diag ? cp : cp + 2 * STAGE, wm, wn, lane, acc);
+    if (more) {
+      float* np = smem + (buf ^ 1) * STAGE;
+      tn_store_chunk<KT>(np, rp, tid);
+      if (!diag) tn_store_chunk<KT>(np + 2 * STAGE, rq, tid);
+    }
+    __syncthreads();
+    buf ^= 1;
   }
 }
 
 template <int KT, bool SYM, bool PARTIAL, bool VEC, int MINW = 2>
 __global__ __launch_bounds__(WG_THREADS, MINW) void tn_gemm_kernel(TnGemmArgs a) {
   extern __shared__ __align__(16) float smem[];
-  constexpr int STAGE = KT * TILE;   // floats per operand per buffer; P buffers, then Q buffers
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -114,36 +167,11 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void tn_gemm_kernel(TnGemmArgs a)
   acc.clear();
 
   if (kbeg < kend) {
-    float4 rp[KT / 8], rq[KT / 8];
-    // interior tiles of an aligned operand take the predicate-free loads for every full chunk
-    const bool inner = VEC && (m0 + TILE <= a.M) && (n0 + TILE <= a.N);
-    auto load = [&](int64_t k0) {
-      if (inner && k0 + KT <= kend) {
-        tn_load_chunk<KT, VEC, true>(a.P, a.ldp, k0, kend, m0, a.M, rp, tid);
-        if (!diag) tn_load_chunk<KT, VEC, true>(a.Q, a.ldq, k0, kend, n0, a.N, rq, tid);
-      } else {
-        tn_load_chunk<KT, VEC, false>(a.P, a.ldp, k0, kend, m0, a.M, rp, tid);
-        if (!diag) tn_load_chunk<KT, VEC, false>(a.Q, a.ldq, k0, kend, n0, a.N, rq, tid);
-      }
-    };
-    load(kbeg);
-    tn_store_chunk<KT>(smem, rp, tid);
-    if (!diag) tn_store_chunk<KT>(smem + 2 * STAGE, rq, tid);
-    __syncthreads();
-    int buf = 0;
-    for (int64_t k0 = kbeg; k0 < kend; k0 += KT) {
-      const bool more = (k0 + KT) < kend;
-      if (more) load(k0 + KT);
-      const float* cp = smem + buf * STAGE;
-      mma_chunk_kmajor<KT>(cp, diag ? cp : cp + 2 * STAGE, wm, wn, lane, acc);
-      if (more) {
-        float* np = smem + (buf ^ 1) * STAGE;
-        tn_store_chunk<KT>(np, rp, tid);
-        if (!diag) tn_store_chunk<KT>(np + 2 * STAGE, rq, tid);
-      }
-      __syncthreads();
-      buf ^= 1;
-    }
+    // interior tiles of an aligned operand whose slice is a whole number of stages take the
+    // predicate-free loads; the two loops are separate so that each has one load variant
+    const bool fast = VEC && (m0 + TILE <= a.M) && (n0 + TILE <= a.N) && ((kend - kbeg) % KT == 0);
+    if (fast) tn_mainloop<KT, VEC, true>(a, smem, kbeg, kend, m0, n0, diag, wm, wn, lane, tid, acc);
+    else tn_mainloop<KT, VEC, false>(a, smem, kbeg, kend, m0, n0, diag, wm, wn, lane, tid, acc);
   }
 
   if (PARTIAL) {
