@@ -42,6 +42,49 @@ __device__ __forceinline__ void decode_upper(int idx, int T, int& bi, int& bj) {
   bj = r + (idx - (r * T - (r * (r - 1)) / 2));
 }
 
+// Tiles are handed out patch by patch (PATCH x PATCH tiles) so that workgroups that run at
+// the same time on one XCD read few distinct operand panels and find them in that XCD's L2.
+constexpr int PATCH = 8;
+constexpr int XCDS = 8;          // workgroup ids go round-robin over the 8 XCDs
+constexpr int XCD_CHUNK = 64;    // consecutive work items given to one XCD
+
+// blockIdx -> work item: each XCD gets runs of XCD_CHUNK consecutive work items.
+__device__ __forceinline__ int xcd_swizzle(int b, int total) {
+  const int group = XCDS * XCD_CHUNK;
+  const int full = (total / group) * group;
+  if (b >= full) return b;
+  const int xcd = b % XCDS, slot = b / XCDS;
+  return (slot / XCD_CHUNK) * group + xcd * XCD_CHUNK + (slot % XCD_CHUNK);
+}
+
+// Patch-major enumeration of a tiles_m x tiles_n grid (general) or of its upper triangle
+// (SYM, tiles_m == tiles_n): index -> (bi, bj).  Walks the patches in row-major order.
+template <bool SYM>
+__device__ __forceinline__ void decode_patch_major(int idx, int tiles_m, int tiles_n, int& bi, int& bj) {
+  const int pm = (tiles_m + PATCH - 1) / PATCH, pn = (tiles_n + PATCH - 1) / PATCH;
+  for (int pi = 0; pi < pm; ++pi) {
+    const int h = min(PATCH, tiles_m - pi * PATCH);
+    for (int pj = SYM ? pi : 0; pj < pn; ++pj) {
+      const int w = min(PATCH, tiles_n - pj * PATCH);
+      const int cnt = (SYM && pi == pj) ? h * (h + 1) / 2 : h * w;
+      if (idx < cnt) {
+        int li, lj;
+        if (SYM && pi == pj) {
+          decode_upper(idx, h, li, lj);
+        } else {
+          li = idx / w;
+          lj = idx - li * w;
+        }
+        bi = pi * PATCH + li;
+        bj = pj * PATCH + lj;
+        return;
+      }
+      idx -= cnt;
+    }
+  }
+  bi = 0; bj = 0;  // not reached for idx < number of tiles
+}
+
 // One k-chunk (KT rows x 128 columns) of an operand in registers: KT / 8 float4 per thread,
 // held as named members so that they stay in registers.
 template <int KT> struct ChunkRegs;
@@ -147,16 +190,11 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void tn_gemm_kernel(TnGemmArgs a)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 
-  const int work = blockIdx.x;
+  const int work = xcd_swizzle(blockIdx.x, a.splits * a.ntiles);
   const int split = work / a.ntiles;
   const int tile = work - split * a.ntiles;
   int bi, bj;
-  if (SYM) {
-    decode_upper(tile, a.tiles_m, bi, bj);
-  } else {
-    bi = tile / a.tiles_n;
-    bj = tile - bi * a.tiles_n;
-  }
+  decode_patch_major<SYM>(tile, a.tiles_m, a.tiles_n, bi, bj);
   const bool diag = SYM && (bi == bj);
   const int64_t m0 = (int64_t)bi * TILE, n0 = (int64_t)bj * TILE;
   const int64_t kbeg = (int64_t)split * a.k_per_split;
@@ -211,7 +249,7 @@ static __global__ __launch_bounds__(WG_THREADS) void tn_reduce_sym_kernel(const 
   const int tid = threadIdx.x;
   const int tile = blockIdx.x;
   int bi, bj;
-  decode_upper(tile, T, bi, bj);
+  decode_patch_major<true>(tile, T, T, bi, bj);
   const int64_t m0 = (int64_t)bi * TILE, n0 = (int64_t)bj * TILE;
   for (int sb = 0; sb < 4; ++sb) {
     // rows sb*32 .. sb*32+31 of the tile: 32 x 128 values, 16 per thread

@@ -8,7 +8,11 @@
 //     from its remaining registers (line 17).  The B x B diagonal blocks of U are packed
 //     once per layer and read as wave-uniform scalars.  E is written transposed so that
 //   * the trailing update W[:, i+B:] -= E U[i:i+B, i+B:] (line 19) is a k-major
-//     fp32 MFMA product of the same kind as the Hessian accumulation.
+//     fp32 MFMA product of the same kind as the Hessian accumulation.  Blocks are taken
+//     in groups of 4: after a block only the remaining columns of its group are updated
+//     (they are needed next); the columns beyond the group receive the 4 blocks' updates
+//     at once as one 4B-deep product.  The sums are the same, re-associated; W beyond
+//     the group is read and written once per group instead of once per block.
 #include "lq_common.h"
 #include "lq_tn_gemm.h"
 
@@ -17,6 +21,7 @@
 namespace {
 
 constexpr int KT = 32;
+constexpr int GROUP = 4;   // blocks whose far-field updates are applied together
 
 // Pack the diagonal B x B blocks of U: ud[blk][j][jj] = U[i0+j][i0+jj] for jj >= j inside the
 // matrix, zero elsewhere; urinv[blk][j] = 1 / U[i0+j][i0+j] (0 outside the matrix).
@@ -44,7 +49,7 @@ QuantPlan make_plan(int64_t r, int64_t c, int B) {
   QuantPlan p;
   p.rpad = lq::ceil_div(r > 0 ? r : 1, lq::QT) * lq::QT;   // one slot per lane of the column kernel
   p.nblk = lq::ceil_div(c, B);
-  p.off_ud = lq::align_up((size_t)p.rpad * B * sizeof(float), 256);
+  p.off_ud = lq::align_up((size_t)p.rpad * B * GROUP * sizeof(float), 256);
   p.off_rinv = p.off_ud + lq::align_up((size_t)p.nblk * B * B * sizeof(float), 256);
   p.total = p.off_rinv + lq::align_up((size_t)p.nblk * B * sizeof(float), 256);
   return p;
@@ -104,37 +109,53 @@ extern "C" lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t l
                      ud, urinv);
   LQ_CHECK_LAUNCH("pack_diag_blocks_kernel");
 
+  // C[:, col0 : col0+ncols] -= Et[0:K, :]^T * U[urow0 : urow0+K, col0 : col0+ncols]
+  auto update = [&](const float* et, int64_t K, int64_t urow0, int64_t col0, int64_t ncols) -> lq_status {
+    lq::TnGemmArgs t;
+    t.P = et; t.ldp = rpad;
+    t.Q = U + urow0 * ldu + col0; t.ldq = ldu;
+    t.C = W + col0; t.ldc = ldw;
+    t.M = r; t.N = ncols; t.K = K;
+    t.alpha = -1.0f;
+    t.tiles_m = (int)lq::ceil_div(r, lq::TILE);
+    t.tiles_n = (int)lq::ceil_div(ncols, lq::TILE);
+    t.ntiles = t.tiles_m * t.tiles_n;
+    t.splits = 1;
+    t.k_per_split = K;
+    t.partial = nullptr;
+    const bool vec = (ldu % 4 == 0) && lq::aligned(t.Q, 16);
+    dim3 grid2((unsigned)t.ntiles), block2(lq::WG_THREADS);
+    if (vec)
+      hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, false, false, true>), grid2, block2, gemm_lds, st, t);
+    else
+      hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, false, false, false>), grid2, block2, gemm_lds, st, t);
+    LQ_CHECK_LAUNCH("tn_gemm_kernel(trailing)");
+    return LQ_OK;
+  };
+
+  float* const et_base = a.Et;
   for (int64_t i0 = 0; i0 < c; i0 += B) {
-    const float* udb = ud + (i0 / B) * B * B;
-    const float* rib = urinv + (i0 / B) * B;
+    const int64_t blk = i0 / B;
+    const int64_t li = blk % GROUP;                       // position inside the group
+    const int64_t gbase = (blk - li) * B;                 // first column of the group
+    const int64_t gend = (gbase + (int64_t)GROUP * B < c) ? gbase + (int64_t)GROUP * B : c;
+    const float* udb = ud + blk * B * B;
+    const float* rib = urinv + blk * B;
     a.i0 = i0;
     a.nb = (int)((c - i0) < B ? (c - i0) : B);
     a.first = (i0 == 0);
+    a.Et = et_base + li * B * rpad;
     lq_status s2 = (B == 128) ? lq::launch_column_128(a, udb, rib, P, st)
                  : (B == 64)  ? lq::launch_column_64(a, udb, rib, P, st)
                               : lq::launch_column_32(a, udb, rib, P, st);
     if (s2 != LQ_OK) return s2;
-    const int64_t rest = c - i0 - a.nb;
-    if (rest > 0) {
-      lq::TnGemmArgs t;
-      t.P = a.Et; t.ldp = rpad;
-      t.Q = U + i0 * ldu + (i0 + B); t.ldq = ldu;
-      t.C = W + (i0 + B); t.ldc = ldw;
-      t.M = r; t.N = rest; t.K = B;
-      t.alpha = -1.0f;
-      t.tiles_m = (int)lq::ceil_div(r, lq::TILE);
-      t.tiles_n = (int)lq::ceil_div(rest, lq::TILE);
-      t.ntiles = t.tiles_m * t.tiles_n;
-      t.splits = 1;
-      t.k_per_split = B;
-      t.partial = nullptr;
-      const bool vec = (ldu % 4 == 0) && lq::aligned(t.Q, 16);
-      dim3 grid2((unsigned)t.ntiles), block2(lq::WG_THREADS);
-      if (vec)
-        hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, false, false, true>), grid2, block2, gemm_lds, st, t);
-      else
-        hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, false, false, false>), grid2, block2, gemm_lds, st, t);
-      LQ_CHECK_LAUNCH("tn_gemm_kernel(trailing)");
+    const int64_t next = i0 + B;
+    if (next < gend) {                                    // rest of the group: needed next
+      s2 = update(a.Et, B, i0, next, gend - next);
+      if (s2 != LQ_OK) return s2;
+    } else if (gend < c) {                                // group finished: everything beyond it
+      s2 = update(et_base, (li + 1) * B, gbase, gend, c - gend);
+      if (s2 != LQ_OK) return s2;
     }
   }
   return LQ_OK;
