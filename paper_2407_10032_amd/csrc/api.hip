@@ -24,6 +24,24 @@ lq_status fail(lq_status code, const char* fmt, ...) {
   return code;
 }
 
+SideStream* side_stream() {
+  struct Slot { bool tried = false; bool ok = false; SideStream s; };
+  static thread_local Slot slots[16];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
+  Slot& sl = slots[dev];
+  if (!sl.tried) {
+    sl.tried = true;
+    bool ok = hipStreamCreateWithFlags(&sl.s.stream, hipStreamNonBlocking) == hipSuccess;
+    for (int i = 0; ok && i < 4; ++i)
+      ok = hipEventCreateWithFlags(&sl.s.fork[i], hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&sl.s.join, hipEventDisableTiming) == hipSuccess;
+    sl.ok = ok;
+    if (!ok) (void)hipGetLastError();
+  }
+  return sl.ok ? &sl.s : nullptr;
+}
+
 int resolve_t(const lq_params* P) {
   if (P->t_override >= 0) return P->t_override;
   // Eq. 8: t = 0.2 T, 0.3 T, 0.4 T for b = 4, 3, 2; floored (2048 is not divisible by 5).

@@ -123,6 +123,9 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(float* __restrict__ A, 
   float* sL = sm;                       // [128][129]
   float* sX = sm + NB * DLD;            // 10 lower blocks of the inverse, [32][33] each
   float* sT = sX + 10 * XBLK;           // 3 temporaries, [32][33] each
+  float* sLc = sT + 3 * XBLK;           // [32][32] compact copy of the current sub-block's factor
+  float* sCol = sLc + 32 * 32;          // [32] current column of the factor
+  float* sRd = sCol + 32;               // [32] reciprocals of the factor's diagonal
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float* tile = A + ((int64_t)kb * NB) * cp + (int64_t)kb * NB;
   for (int f = tid; f < NB * NB / 4; f += 256) {
@@ -140,7 +143,8 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(float* __restrict__ A, 
       float a[32];
 #pragma unroll
       for (int k = 0; k < 32; ++k) a[k] = sL[(c0 + ri) * DLD + c0 + k];
-      // right-looking Cholesky of the 32 x 32 sub-block, row ri in this lane
+      // Right-looking Cholesky of the 32 x 32 sub-block, row ri in this lane.  Column j of
+      // the factor goes through LDS and comes back as wave-uniform broadcast reads.
 #pragma unroll
       for (int j = 0; j < 32; ++j) {
         float pj = lane_bcast(a[j], j);
@@ -152,24 +156,48 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(float* __restrict__ A, 
         const float dj = sqrtf(pj);
         const float rj = 1.0f / dj;
         a[j] = (ri == j) ? dj : a[j] * rj;
+        if (j < 31) {
+          sCol[ri] = a[j];
+          if (lane == 0) sRd[j] = rj;
 #pragma unroll
-        for (int k = j + 1; k < 32; ++k) a[k] = fmaf(-a[j], lane_bcast(a[j], k), a[k]);
+          for (int k4 = (j + 1) / 4; k4 < 8; ++k4) {
+            const float4 cv = *reinterpret_cast<const float4*>(sCol + 4 * k4);
+            if (4 * k4 + 0 > j) a[4 * k4 + 0] = fmaf(-a[j], cv.x, a[4 * k4 + 0]);
+            if (4 * k4 + 1 > j) a[4 * k4 + 1] = fmaf(-a[j], cv.y, a[4 * k4 + 1]);
+            if (4 * k4 + 2 > j) a[4 * k4 + 2] = fmaf(-a[j], cv.z, a[4 * k4 + 2]);
+            if (4 * k4 + 3 > j) a[4 * k4 + 3] = fmaf(-a[j], cv.w, a[4 * k4 + 3]);
+          }
+        } else if (lane == 0) {
+          sRd[j] = rj;
+        }
       }
-      // inverse of the sub-block's factor, column ri in this lane
-      float x[32];
-#pragma unroll
-      for (int i = 0; i < 32; ++i) {
-        float acc = 0.0f;
-#pragma unroll
-        for (int k = 0; k < i; ++k) acc = fmaf(lane_bcast(a[k], i), x[k], acc);
-        x[i] = ((ri == i) ? 1.0f : -acc) / lane_bcast(a[i], i);
-      }
+      // factor rows to LDS: the block itself and an aligned compact copy for the inverse
       if (lane < 32) {
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
           if (k <= ri) sL[(c0 + ri) * DLD + c0 + k] = a[k];
-          sX[xblk(kk, kk) + k * XLD + ri] = (k >= ri) ? x[k] : 0.0f;
+          sLc[ri * 32 + k] = (k <= ri) ? a[k] : 0.0f;
         }
+      }
+      // inverse of the sub-block's factor, column ri in this lane: row i of the factor is
+      // read as broadcast float4s, x[i] = (delta_i,ri - sum_k L[i][k] x[k]) / L[i][i]
+      float x[32];
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        float acc0 = 0.0f, acc1 = 0.0f;
+#pragma unroll
+        for (int k4 = 0; k4 < (i + 3) / 4; ++k4) {
+          const float4 lv = *reinterpret_cast<const float4*>(sLc + i * 32 + 4 * k4);
+          if (4 * k4 + 0 < i) acc0 = fmaf(lv.x, x[4 * k4 + 0], acc0);
+          if (4 * k4 + 1 < i) acc1 = fmaf(lv.y, x[4 * k4 + 1], acc1);
+          if (4 * k4 + 2 < i) acc0 = fmaf(lv.z, x[4 * k4 + 2], acc0);
+          if (4 * k4 + 3 < i) acc1 = fmaf(lv.w, x[4 * k4 + 3], acc1);
+        }
+        x[i] = ((ri == i) ? 1.0f : -(acc0 + acc1)) * sRd[i];
+      }
+      if (lane < 32) {
+#pragma unroll
+        for (int k = 0; k < 32; ++k) sX[xblk(kk, kk) + k * XLD + ri] = (k >= ri) ? x[k] : 0.0f;
       }
     }
     __syncthreads();
@@ -228,11 +256,17 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(float* __restrict__ A, 
   }
 
   float* dinv = Dinv + (int64_t)kb * NB * NB;
-  for (int f = tid; f < NB * NB; f += 256) {
-    int row = f >> 7, col = f & 127;
-    tile[(int64_t)row * cp + col] = (col <= row) ? sL[row * DLD + col] : 0.0f;
-    int ib = row >> 5, jb = col >> 5;
-    dinv[f] = (jb <= ib) ? sX[xblk(ib, jb) + (row & 31) * XLD + (col & 31)] : 0.0f;
+  for (int f = tid; f < NB * NB / 4; f += 256) {
+    const int row = f >> 5, col = 4 * (f & 31);
+    const int ib = row >> 5, jb = col >> 5;
+    float l[4], xv[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      l[e] = (col + e <= row) ? sL[row * DLD + col + e] : 0.0f;
+      xv[e] = (jb <= ib) ? sX[xblk(ib, jb) + (row & 31) * XLD + ((col + e) & 31)] : 0.0f;
+    }
+    *reinterpret_cast<float4*>(tile + (int64_t)row * cp + col) = make_float4(l[0], l[1], l[2], l[3]);
+    *reinterpret_cast<float4*>(dinv + row * NB + col) = make_float4(xv[0], xv[1], xv[2], xv[3]);
   }
 }
 
@@ -402,7 +436,7 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
   const int64_t cp = plan.cp;
   const int nb = plan.nb;
 
-  const size_t potrf_lds = (NB * DLD + 13 * 32 * 33) * sizeof(float);
+  const size_t potrf_lds = (NB * DLD + 13 * 32 * 33 + 32 * 32 + 64) * sizeof(float);
   static bool attr_done = false;
   if (!attr_done) {
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)potrf_diag_kernel,
@@ -416,8 +450,32 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
   hipLaunchKernelGGL(flip_damp_kernel, g2, dim3(256), 0, st, H, ldh, c, cp, (const float*)scal, A);
   LQ_CHECK_LAUNCH("flip_damp_kernel");
 
+  // The inverse workspace starts from zero; cleared before the factorization so that the
+  // inverse chain can start as soon as the first panel exists.
+  int64_t n = cp * cp;
+  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)lq::ceil_div(n, 1024)), dim3(256), 0, st, Xb, n, 0.0f);
+  LQ_CHECK_LAUNCH("fill_kernel");
+
+  // Two chains: the factorization (diagonal block, panel, trailing update per step) on
+  // the caller's stream, and the triangular inverse on a side stream.  Step i of the
+  // inverse needs only the panels up to i, so it follows the factorization one step behind
+  // instead of waiting for all of it.
+  lq::SideStream* side = lq::side_stream();
+  hipStream_t sinv = side ? side->stream : st;
+
   ChArgs a;
   a.A = A; a.Xb = Xb; a.Dinv = Dinv; a.cp = cp;
+  auto inverse_step = [&](int i) -> lq_status {
+    ChArgs b = a;
+    b.step = i;
+    hipLaunchKernelGGL(chol_gemm_kernel<CH_TRI_ROW>, dim3(i + 1), dim3(WG_THREADS), 0, sinv, b);
+    LQ_CHECK_LAUNCH("chol_gemm_kernel<tri_row>");
+    if (i + 1 < nb) {
+      hipLaunchKernelGGL(chol_gemm_kernel<CH_TRI_UPD>, dim3((nb - i - 1) * (i + 1)), dim3(WG_THREADS), 0, sinv, b);
+      LQ_CHECK_LAUNCH("chol_gemm_kernel<tri_upd>");
+    }
+    return LQ_OK;
+  };
   for (int kb = 0; kb < nb; ++kb) {
     hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(256), potrf_lds, st, A, cp, kb, Dinv, info, c);
     LQ_CHECK_LAUNCH("potrf_diag_kernel");
@@ -426,21 +484,27 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
       a.step = kb;
       hipLaunchKernelGGL(chol_gemm_kernel<CH_PANEL>, dim3(m), dim3(WG_THREADS), 0, st, a);
       LQ_CHECK_LAUNCH("chol_gemm_kernel<panel>");
+    }
+    if (side) {
+      hipEvent_t ev = side->fork[kb & 3];
+      LQ_CHECK_HIP(hipEventRecord(ev, st));
+      LQ_CHECK_HIP(hipStreamWaitEvent(side->stream, ev, 0));
+      lq_status si = inverse_step(kb);
+      if (si != LQ_OK) return si;
+    }
+    if (m > 0) {
+      a.step = kb;
       hipLaunchKernelGGL(chol_gemm_kernel<CH_SYRK>, dim3(m * (m + 1) / 2), dim3(WG_THREADS), 0, st, a);
       LQ_CHECK_LAUNCH("chol_gemm_kernel<syrk>");
     }
   }
-
-  int64_t n = cp * cp;
-  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)lq::ceil_div(n, 1024)), dim3(256), 0, st, Xb, n, 0.0f);
-  LQ_CHECK_LAUNCH("fill_kernel");
-  for (int i = 0; i < nb; ++i) {
-    a.step = i;
-    hipLaunchKernelGGL(chol_gemm_kernel<CH_TRI_ROW>, dim3(i + 1), dim3(WG_THREADS), 0, st, a);
-    LQ_CHECK_LAUNCH("chol_gemm_kernel<tri_row>");
-    if (i + 1 < nb) {
-      hipLaunchKernelGGL(chol_gemm_kernel<CH_TRI_UPD>, dim3((nb - i - 1) * (i + 1)), dim3(WG_THREADS), 0, st, a);
-      LQ_CHECK_LAUNCH("chol_gemm_kernel<tri_upd>");
+  if (side) {
+    LQ_CHECK_HIP(hipEventRecord(side->join, side->stream));
+    LQ_CHECK_HIP(hipStreamWaitEvent(st, side->join, 0));
+  } else {
+    for (int i = 0; i < nb; ++i) {
+      lq_status si = inverse_step(i);
+      if (si != LQ_OK) return si;
     }
   }
 

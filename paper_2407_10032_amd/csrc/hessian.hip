@@ -11,9 +11,9 @@
 
 namespace {
 
-constexpr int KT = 16;                       // tokens per LDS stage: 32 KB of LDS and < 128 VGPRs,
-                                             // so four workgroups share a compute unit
-constexpr int MINW = 3;
+constexpr int KT = 32;                       // tokens per LDS stage (64 KB of LDS, two workgroups per CU;
+                                             // 16-token stages at four per CU measured 2 % slower)
+constexpr int MINW = 2;
 constexpr int64_t MIN_TOKENS_PER_SPLIT = 256;
 constexpr int64_t TARGET_WORKGROUPS = 16384; // ~32 resident rounds of 2 workgroups per CU: short tail
 

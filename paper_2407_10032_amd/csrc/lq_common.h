@@ -19,6 +19,18 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// A second stream and a few events, per host thread and device, created on first use and
+// kept for the life of the thread.  Calls use it to run independent kernel chains side by
+// side with the caller's stream (fork and join through events, so the work is still
+// ordered after everything enqueued before the call and before everything enqueued after
+// it).  Returns nullptr if the objects cannot be created; callers then stay on one stream.
+struct SideStream {
+  hipStream_t stream;
+  hipEvent_t fork[4];   // recorded on the caller's stream, waited on by the side stream
+  hipEvent_t join;      // recorded on the side stream, waited on by the caller's stream
+};
+SideStream* side_stream();
+
 // Resolve Eq. 8's shrink limit t for the given parameters; returns < 0 if invalid.
 int resolve_t(const lq_params* P);
 // Validate the fields every call shares; returns LQ_OK or sets the error text.
