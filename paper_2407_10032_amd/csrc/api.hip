@@ -24,12 +24,13 @@ lq_status fail(lq_status code, const char* fmt, ...) {
   return code;
 }
 
-SideStream* side_stream() {
+SideStream* side_stream(int which) {
   struct Slot { bool tried = false; bool ok = false; SideStream s; };
-  static thread_local Slot slots[16];
+  static thread_local Slot slots[16][2];
   int dev = 0;
+  if (which < 0 || which > 1) return nullptr;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
-  Slot& sl = slots[dev];
+  Slot& sl = slots[dev][which];
   if (!sl.tried) {
     sl.tried = true;
     bool ok = hipStreamCreateWithFlags(&sl.s.stream, hipStreamNonBlocking) == hipSuccess;

@@ -460,7 +460,7 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
   // the caller's stream, and the triangular inverse on a side stream.  Step i of the
   // inverse needs only the panels up to i, so it follows the factorization one step behind
   // instead of waiting for all of it.
-  lq::SideStream* side = lq::side_stream();
+  lq::SideStream* side = lq::side_stream(0);
   hipStream_t sinv = side ? side->stream : st;
 
   ChArgs a;

@@ -19,7 +19,7 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// A second stream and a few events, per host thread and device, created on first use and
+// Side streams (two) and a few events each, per host thread and device, created on first use and
 // kept for the life of the thread.  Calls use it to run independent kernel chains side by
 // side with the caller's stream (fork and join through events, so the work is still
 // ordered after everything enqueued before the call and before everything enqueued after
@@ -29,7 +29,7 @@ struct SideStream {
   hipEvent_t fork[4];   // recorded on the caller's stream, waited on by the side stream
   hipEvent_t join;      // recorded on the side stream, waited on by the caller's stream
 };
-SideStream* side_stream();
+SideStream* side_stream(int which = 0);   // which: 0 or 1
 
 // Resolve Eq. 8's shrink limit t for the given parameters; returns < 0 if invalid.
 int resolve_t(const lq_params* P);
