@@ -25,6 +25,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 FP32_MFMA_PEAK_TFLOPS = 157.3
+# HBM-side bytes of one Gram-kernel launch on the c2 workload, from the two rocprofv3 --pmc
+# runs (FETCH_SIZE, WRITE_SIZE, each scaled by a plain copy of known size) summarised in
+# profiles/bench_c2_gram_kernel_counters.md.  Only valid for that workload.
+GRAM_TRAFFIC_BYTES_C2 = 61.1e9
 
 
 def log(msg):
@@ -170,7 +174,8 @@ def main():
                                 "quantize_layer": stage_ms[3]}},
         "roofline": {"bound": "mfma", "kernel": "tn_gemm_kernel (H += 2 X^T X, upper tiles) + partial-sum reduce",
                      "achieved": achieved, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / FP32_MFMA_PEAK_TFLOPS, "traffic": None,
+                     "frac": achieved / FP32_MFMA_PEAK_TFLOPS,
+                     "traffic": GRAM_TRAFFIC_BYTES_C2 if (cfg.name == "c2" and not args.tokens) else None,
                      "flops_per_launch": flops, "ms_per_launch": float(stage_ms[0])},
     }
     if not args.no_cpu_baseline:
