@@ -105,14 +105,33 @@ __global__ __launch_bounds__(QT) void column_block_kernel(ColArgs a, const float
   }
   for (int j = tid; j < B; j += QT) sRinv[j] = urinv[j];
 
-  // this wavefront's 64 x B piece of W -> LDS (rows past r and columns past c read as zero)
+  // the row's grid first (its loads overlap the block load below)
+  typename GridVec<K>::type g, mid;
+  float S = 1.0f, Z = 0.0f, invS = 1.0f;
+#pragma unroll
+  for (int m = 0; m < K; ++m) g[m] = (!AFF && valid) ? a.grid[row * K + m] : 0.0f;
+
+  // this wavefront's 64 x B piece of W -> LDS (rows past r and columns past c read as zero);
+  // eight 16-byte loads are in flight before their values are written to LDS
   if (a.vecw && nb == B) {
-    for (int f = lane; f < 64 * (B / 4); f += 64) {
-      int rr = f / (B / 4), c4 = f % (B / 4);
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (row0 + rr < a.r) v = *reinterpret_cast<const float4*>(a.W + (row0 + rr) * a.ldw + a.i0 + 4 * c4);
-      float* d = sW + rr * LD + 4 * c4;
-      d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+    constexpr int PER_LANE = 64 * (B / 4) / 64;
+    static_assert(PER_LANE % 8 == 0, "block load is unrolled by eight");
+    for (int it = 0; it < PER_LANE; it += 8) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int f = lane + (it + u) * 64;
+        const int rr = f / (B / 4), c4 = f % (B / 4);
+        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row0 + rr < a.r) v[u] = *reinterpret_cast<const float4*>(a.W + (row0 + rr) * a.ldw + a.i0 + 4 * c4);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int f = lane + (it + u) * 64;
+        const int rr = f / (B / 4), c4 = f % (B / 4);
+        float* d = sW + rr * LD + 4 * c4;
+        d[0] = v[u].x; d[1] = v[u].y; d[2] = v[u].z; d[3] = v[u].w;
+      }
     }
   } else {
     for (int f = lane; f < 64 * B; f += 64) {
@@ -121,10 +140,6 @@ __global__ __launch_bounds__(QT) void column_block_kernel(ColArgs a, const float
     }
   }
 
-  typename GridVec<K>::type g, mid;
-  float S = 1.0f, Z = 0.0f, invS = 1.0f;
-#pragma unroll
-  for (int m = 0; m < K; ++m) g[m] = (!AFF && valid) ? a.grid[row * K + m] : 0.0f;
 #pragma unroll
   for (int m = 0; m < K; ++m) mid[m] = (m < K - 1) ? 0.5f * (g[m] + g[m < K - 1 ? m + 1 : m]) : 0.0f;
   __syncthreads();
@@ -141,6 +156,12 @@ __global__ __launch_bounds__(QT) void column_block_kernel(ColArgs a, const float
     uint32_t pk[SB / 4];
 #pragma unroll
     for (int q4 = 0; q4 < SB / 4; ++q4) pk[q4] = 0u;
+    // B operand of the first tile updated after this sub-block: loaded now, used after the
+    // column phase (rows cb.. of the packed U block, columns of the next sub-block)
+    float bpre[SB / 2];
+#pragma unroll
+    for (int kk = 0; kk < SB / 2; ++kk)
+      bpre[kk] = (sb + 1 < NSB) ? ud[(cb + 2 * kk + hl) * B + (sb + 1) * SB + ml] : 0.0f;
 
     // Columns past the end of a ragged last block hold zeros and have 1 / U_jj = 0, so
     // they produce E = 0 and change nothing; only the stores are guarded.
@@ -203,8 +224,13 @@ __global__ __launch_bounds__(QT) void column_block_kernel(ColArgs a, const float
       }
       for (int t = sb + 1; t < NSB; ++t) {
         float b[SB / 2];
+        if (t == sb + 1) {
 #pragma unroll
-        for (int kk = 0; kk < SB / 2; ++kk) b[kk] = ud[(cb + 2 * kk + hl) * B + t * SB + ml];
+          for (int kk = 0; kk < SB / 2; ++kk) b[kk] = bpre[kk];
+        } else {
+#pragma unroll
+          for (int kk = 0; kk < SB / 2; ++kk) b[kk] = ud[(cb + 2 * kk + hl) * B + t * SB + ml];
+        }
         floatx16 c_lo, c_hi;
         float* tl = sW + t * SB + ml;
 #pragma unroll
@@ -230,6 +256,7 @@ __global__ __launch_bounds__(QT) void column_block_kernel(ColArgs a, const float
 
   // W_hat of the block back to global memory, row by row (coalesced)
   if (a.vecw && nb == B) {
+#pragma unroll 8
     for (int f = lane; f < 64 * (B / 4); f += 64) {
       int rr = f / (B / 4), c4 = f % (B / 4);
       if (row0 + rr < a.r) {
