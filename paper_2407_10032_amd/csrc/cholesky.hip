@@ -357,6 +357,154 @@ __global__ __launch_bounds__(WG_THREADS, 2) void chol_gemm_kernel(ChArgs a) {
       }
 }
 
+// The same four products cut into smaller output tiles, for steps that have too few
+// 128 x 128 tiles to occupy the chip (every step at c <= 8192 or so): one workgroup
+// computes a TM x TN piece with all 128 k-values of both operands loaded into LDS at once
+// (one barrier, no stage loop), so a step's latency is one short workgroup instead of one
+// long one.  In-place modes are only cut along the dimension they do not read across:
+// the panel by rows (64 x 128), the inverse's row update by columns (128 x 64); the two
+// trailing updates, which write tiles they do not read, into 64 x 64 quarters.
+constexpr int SLD = 129;   // LDS leading dimension of a row-major 128-deep operand
+
+template <int ROWS>
+__device__ __forceinline__ void fill_rows_k128(float* __restrict__ s, const float* __restrict__ src,
+                                               int64_t ld, int tid) {
+  // ROWS x 128 values, src[row*ld + k] -> s[row*SLD + k]; coalesced 16-byte global loads
+#pragma unroll
+  for (int p = 0; p < ROWS / 8; ++p) {
+    const int f = tid + p * WG_THREADS;
+    const int row = f >> 5, k4 = f & 31;
+    const float4 v = *reinterpret_cast<const float4*>(src + (int64_t)row * ld + 4 * k4);
+    float* d = s + row * SLD + 4 * k4;
+    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+  }
+}
+
+template <int COLS>
+__device__ __forceinline__ void fill_kmajor_k128(float* __restrict__ s, const float* __restrict__ src,
+                                                 int64_t ld, int tid) {
+  // 128 k-rows x COLS values, src[k*ld + n] -> s[k*COLS + n]
+  constexpr int F4_PER_ROW = COLS / 4;
+#pragma unroll
+  for (int p = 0; p < 128 * F4_PER_ROW / WG_THREADS; ++p) {
+    const int f = tid + p * WG_THREADS;
+    const int k = f / F4_PER_ROW, c4 = f % F4_PER_ROW;
+    *reinterpret_cast<float4*>(s + k * COLS + 4 * c4) =
+        *reinterpret_cast<const float4*>(src + (int64_t)k * ld + 4 * c4);
+  }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(WG_THREADS) void chol_small_kernel(ChArgs a) {
+  constexpr bool B_KMAJOR = (MODE == CH_TRI_ROW || MODE == CH_TRI_UPD);
+  constexpr bool SUBTRACT = (MODE == CH_SYRK || MODE == CH_TRI_UPD);
+  constexpr int TM = (MODE == CH_TRI_ROW) ? 128 : 64;
+  constexpr int TN = (MODE == CH_PANEL) ? 128 : 64;
+  constexpr int NA = TM / 64, NBN = TN / 64;    // 32 x 32 accumulators per wave: NA x NBN
+  extern __shared__ __align__(16) float ssm[];
+  float* sA = ssm;                               // [TM][SLD]
+  float* sB = ssm + TM * SLD;                    // [TN][SLD] or [128][TN]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int ml = lane & 31, kl = lane >> 5;
+  const int b = blockIdx.x;
+  const int64_t cp = a.cp;
+
+  const float* Aop; int64_t lda;
+  const float* Bop; int64_t ldb;
+  float* Out; int64_t ldo;
+  if (MODE == CH_PANEL) {
+    const int64_t i = a.step + 1 + (b >> 1);
+    const int sr = b & 1;
+    Aop = a.A + (i * NB + sr * 64) * cp + (int64_t)a.step * NB; lda = cp;
+    Bop = a.Dinv + (int64_t)a.step * NB * NB; ldb = NB;
+    Out = a.A + (i * NB + sr * 64) * cp + (int64_t)a.step * NB; ldo = cp;
+  } else if (MODE == CH_SYRK) {
+    const int big = b >> 2, sr = (b >> 1) & 1, sc = b & 1;
+    int ii = (int)((sqrtf(8.0f * (float)big + 1.0f) - 1.0f) * 0.5f);
+    while (ii * (ii + 1) / 2 > big) --ii;
+    while ((ii + 1) * (ii + 2) / 2 <= big) ++ii;
+    const int jj = big - ii * (ii + 1) / 2;
+    const int64_t i = a.step + 1 + ii, j = a.step + 1 + jj;
+    Aop = a.A + (i * NB + sr * 64) * cp + (int64_t)a.step * NB; lda = cp;
+    Bop = a.A + (j * NB + sc * 64) * cp + (int64_t)a.step * NB; ldb = cp;
+    Out = a.A + (i * NB + sr * 64) * cp + j * NB + sc * 64; ldo = cp;
+  } else if (MODE == CH_TRI_ROW) {
+    const int64_t i = a.step, k = b >> 1;
+    const int sc = b & 1;
+    Out = a.Xb + (i * NB) * cp + k * NB + sc * 64; ldo = cp;
+    if (k == i) {
+      const float* src = a.Dinv + i * NB * NB + sc * 64;
+      for (int f = tid; f < NB * 16; f += WG_THREADS) {
+        const int row = f >> 4, c4 = f & 15;
+        *reinterpret_cast<float4*>(Out + (int64_t)row * ldo + 4 * c4) =
+            *reinterpret_cast<const float4*>(src + row * NB + 4 * c4);
+      }
+      return;
+    }
+    Aop = a.Dinv + i * NB * NB; lda = NB;
+    Bop = Out; ldb = cp;
+  } else {
+    const int64_t i = a.step;
+    const int big = b >> 2, sr = (b >> 1) & 1, sc = b & 1;
+    const int jj = big / (int)(i + 1), k = big - jj * (int)(i + 1);
+    const int64_t j = i + 1 + jj;
+    Aop = a.A + (j * NB + sr * 64) * cp + i * NB; lda = cp;
+    Bop = a.Xb + (i * NB) * cp + (int64_t)k * NB + sc * 64; ldb = cp;
+    Out = a.Xb + (j * NB + sr * 64) * cp + (int64_t)k * NB + sc * 64; ldo = cp;
+  }
+
+  fill_rows_k128<TM>(sA, Aop, lda, tid);
+  if (B_KMAJOR) fill_kmajor_k128<TN>(sB, Bop, ldb, tid);
+  else fill_rows_k128<TN>(sB, Bop, ldb, tid);
+  __syncthreads();
+
+  lq::floatx16 acc[NA][NBN];
+#pragma unroll
+  for (int x = 0; x < NA; ++x)
+#pragma unroll
+    for (int y = 0; y < NBN; ++y)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.0f;
+
+  const float* pa = sA + (wm * (TM / 2) + ml) * SLD + kl;
+  const float* pb = B_KMAJOR ? sB + kl * TN + wn * (TN / 2) + ml : sB + (wn * (TN / 2) + ml) * SLD + kl;
+#pragma unroll 8
+  for (int k = 0; k < 128; k += 2) {
+    float av[NA], bv[NBN];
+#pragma unroll
+    for (int x = 0; x < NA; ++x) av[x] = pa[x * 32 * SLD + k];
+#pragma unroll
+    for (int y = 0; y < NBN; ++y) bv[y] = B_KMAJOR ? pb[k * TN + y * 32] : pb[y * 32 * SLD + k];
+#pragma unroll
+    for (int x = 0; x < NA; ++x)
+#pragma unroll
+      for (int y = 0; y < NBN; ++y)
+        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[x], bv[y], acc[x][y], 0, 0, 0);
+  }
+
+#pragma unroll
+  for (int x = 0; x < NA; ++x)
+#pragma unroll
+    for (int y = 0; y < NBN; ++y)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = wm * (TM / 2) + x * 32 + 8 * (v >> 2) + 4 * kl + (v & 3);
+        const int col = wn * (TN / 2) + y * 32 + ml;
+        float* o = Out + (int64_t)row * ldo + col;
+        if (SUBTRACT) *o -= acc[x][y][v];
+        else *o = acc[x][y][v];
+      }
+}
+
+template <int MODE>
+constexpr size_t chol_small_lds() {
+  constexpr int TM = (MODE == CH_TRI_ROW) ? 128 : 64;
+  constexpr int TN = (MODE == CH_PANEL) ? 128 : 64;
+  constexpr bool BK = (MODE == CH_TRI_ROW || MODE == CH_TRI_UPD);
+  return (size_t)(TM * SLD + (BK ? 128 * TN : TN * SLD)) * sizeof(float);
+}
+
 // d[c-1-q] = sum_{p=q}^{c-1} Xb[p][q]^2 : column norms of L^-1 = diag(H_d^-1) reversed.
 // 32 columns per workgroup, 8 row-strided partial sums per column added in a fixed order.
 __global__ __launch_bounds__(256) void colnorm_kernel(const float* __restrict__ Xb, int64_t cp,
@@ -441,6 +589,14 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
   if (!attr_done) {
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)potrf_diag_kernel,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)potrf_lds));
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)chol_small_kernel<CH_PANEL>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)chol_small_lds<CH_PANEL>()));
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)chol_small_kernel<CH_SYRK>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)chol_small_lds<CH_SYRK>()));
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)chol_small_kernel<CH_TRI_ROW>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)chol_small_lds<CH_TRI_ROW>()));
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)chol_small_kernel<CH_TRI_UPD>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)chol_small_lds<CH_TRI_UPD>()));
     attr_done = true;
   }
 
@@ -465,15 +621,37 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
 
   ChArgs a;
   a.A = A; a.Xb = Xb; a.Dinv = Dinv; a.cp = cp;
+  // A launch with few 128 x 128 tiles is cut into smaller pieces (see chol_small_kernel).
+  constexpr int SMALL_LIMIT = 768;
+  auto launch = [&](int mode, int big_tiles, hipStream_t sx, const ChArgs& arg) -> lq_status {
+    const bool small = big_tiles <= SMALL_LIMIT;
+    switch (mode) {
+      case CH_PANEL:
+        if (small) hipLaunchKernelGGL(chol_small_kernel<CH_PANEL>, dim3(2 * big_tiles), dim3(WG_THREADS), chol_small_lds<CH_PANEL>(), sx, arg);
+        else hipLaunchKernelGGL(chol_gemm_kernel<CH_PANEL>, dim3(big_tiles), dim3(WG_THREADS), 0, sx, arg);
+        break;
+      case CH_SYRK:
+        if (small) hipLaunchKernelGGL(chol_small_kernel<CH_SYRK>, dim3(4 * big_tiles), dim3(WG_THREADS), chol_small_lds<CH_SYRK>(), sx, arg);
+        else hipLaunchKernelGGL(chol_gemm_kernel<CH_SYRK>, dim3(big_tiles), dim3(WG_THREADS), 0, sx, arg);
+        break;
+      case CH_TRI_ROW:
+        if (small) hipLaunchKernelGGL(chol_small_kernel<CH_TRI_ROW>, dim3(2 * big_tiles), dim3(WG_THREADS), chol_small_lds<CH_TRI_ROW>(), sx, arg);
+        else hipLaunchKernelGGL(chol_gemm_kernel<CH_TRI_ROW>, dim3(big_tiles), dim3(WG_THREADS), 0, sx, arg);
+        break;
+      default:
+        if (small) hipLaunchKernelGGL(chol_small_kernel<CH_TRI_UPD>, dim3(4 * big_tiles), dim3(WG_THREADS), chol_small_lds<CH_TRI_UPD>(), sx, arg);
+        else hipLaunchKernelGGL(chol_gemm_kernel<CH_TRI_UPD>, dim3(big_tiles), dim3(WG_THREADS), 0, sx, arg);
+        break;
+    }
+    LQ_CHECK_LAUNCH("cholesky tile product");
+    return LQ_OK;
+  };
   auto inverse_step = [&](int i) -> lq_status {
     ChArgs b = a;
     b.step = i;
-    hipLaunchKernelGGL(chol_gemm_kernel<CH_TRI_ROW>, dim3(i + 1), dim3(WG_THREADS), 0, sinv, b);
-    LQ_CHECK_LAUNCH("chol_gemm_kernel<tri_row>");
-    if (i + 1 < nb) {
-      hipLaunchKernelGGL(chol_gemm_kernel<CH_TRI_UPD>, dim3((nb - i - 1) * (i + 1)), dim3(WG_THREADS), 0, sinv, b);
-      LQ_CHECK_LAUNCH("chol_gemm_kernel<tri_upd>");
-    }
+    lq_status s1 = launch(CH_TRI_ROW, i + 1, sinv, b);
+    if (s1 != LQ_OK) return s1;
+    if (i + 1 < nb) return launch(CH_TRI_UPD, (nb - i - 1) * (i + 1), sinv, b);
     return LQ_OK;
   };
   for (int kb = 0; kb < nb; ++kb) {
@@ -482,8 +660,8 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
     int m = nb - kb - 1;
     if (m > 0) {
       a.step = kb;
-      hipLaunchKernelGGL(chol_gemm_kernel<CH_PANEL>, dim3(m), dim3(WG_THREADS), 0, st, a);
-      LQ_CHECK_LAUNCH("chol_gemm_kernel<panel>");
+      lq_status sp = launch(CH_PANEL, m, st, a);
+      if (sp != LQ_OK) return sp;
     }
     if (side) {
       hipEvent_t ev = side->fork[kb & 3];
@@ -494,8 +672,8 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
     }
     if (m > 0) {
       a.step = kb;
-      hipLaunchKernelGGL(chol_gemm_kernel<CH_SYRK>, dim3(m * (m + 1) / 2), dim3(WG_THREADS), 0, st, a);
-      LQ_CHECK_LAUNCH("chol_gemm_kernel<syrk>");
+      lq_status ss = launch(CH_SYRK, m * (m + 1) / 2, st, a);
+      if (ss != LQ_OK) return ss;
     }
   }
   if (side) {
