@@ -239,6 +239,57 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void tn_gemm_kernel(TnGemmArgs a)
   }
 }
 
+// Short products (K <= 128, few output tiles): C[64 x 64 tile] += alpha * P^T Q with all K
+// rows of both operand panels loaded into LDS at once.  Used for the updates inside a
+// group of blocks in the column loop, where a 128 x 128 tiling would leave most of the chip
+// idle and a stage loop would only add latency.  LDS: 2 x 128 x 64 floats.
+template <bool VEC>
+__global__ __launch_bounds__(WG_THREADS) void tn_small_kernel(TnGemmArgs a) {
+  constexpr int ST = 64;                     // tile edge
+  __shared__ __align__(16) float sP[128 * ST];
+  __shared__ __align__(16) float sQ[128 * ST];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int ml = lane & 31, kl = lane >> 5;
+  const int bi = blockIdx.x / a.tiles_n, bj = blockIdx.x - bi * a.tiles_n;   // tiles_* count 64-tiles here
+  const int64_t m0 = (int64_t)bi * ST, n0 = (int64_t)bj * ST;
+  const int K = (int)a.K;                    // <= 128, even
+
+  const bool inner = VEC && (m0 + ST <= a.M) && (n0 + ST <= a.N);
+  for (int f = tid; f < 128 * (ST / 4); f += WG_THREADS) {
+    const int k = f / (ST / 4), c4 = f % (ST / 4);
+    float4 p = make_float4(0.f, 0.f, 0.f, 0.f), q = p;
+    if (k < K) {
+      if (inner) {
+        p = *reinterpret_cast<const float4*>(a.P + (int64_t)k * a.ldp + m0 + 4 * c4);
+        q = *reinterpret_cast<const float4*>(a.Q + (int64_t)k * a.ldq + n0 + 4 * c4);
+      } else {
+        p = tn_load_guarded<VEC>(a.P, a.ldp, k, K, m0 + 4 * c4, a.M);
+        q = tn_load_guarded<VEC>(a.Q, a.ldq, k, K, n0 + 4 * c4, a.N);
+      }
+    }
+    *reinterpret_cast<float4*>(sP + k * ST + 4 * c4) = p;
+    *reinterpret_cast<float4*>(sQ + k * ST + 4 * c4) = q;
+  }
+  __syncthreads();
+
+  floatx16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+  const float* pp = sP + kl * ST + wm * 32 + ml;
+  const float* pq = sQ + kl * ST + wn * 32 + ml;
+#pragma unroll 8
+  for (int k = 0; k < 128; k += 2)
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pp[k * ST], pq[k * ST], acc, 0, 0, 0);
+
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int64_t row = m0 + wm * 32 + 8 * (v >> 2) + 4 * kl + (v & 3);
+    const int64_t col = n0 + wn * 32 + ml;
+    if (row < a.M && col < a.N) a.C[row * a.ldc + col] += a.alpha * acc[v];
+  }
+}
+
 // Sum the token-split partial tiles in split order and add alpha * sum to C, writing
 // the tile at (bi, bj) and its transpose at (bj, bi).  One workgroup per upper tile.
 static __global__ __launch_bounds__(WG_THREADS) void tn_reduce_sym_kernel(const float* __restrict__ partial,

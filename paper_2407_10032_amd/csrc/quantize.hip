@@ -124,7 +124,18 @@ extern "C" lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t l
     t.k_per_split = K;
     t.partial = nullptr;
     const bool vec = (ldu % 4 == 0) && lq::aligned(t.Q, 16);
-    dim3 grid2((unsigned)t.ntiles), block2(lq::WG_THREADS);
+    dim3 block2(lq::WG_THREADS);
+    if (K <= 128 && t.ntiles <= 512) {
+      // short and narrow: 64 x 64 tiles, one LDS fill per workgroup
+      t.tiles_m = (int)lq::ceil_div(r, 64);
+      t.tiles_n = (int)lq::ceil_div(ncols, 64);
+      dim3 grid3((unsigned)(t.tiles_m * t.tiles_n));
+      if (vec) hipLaunchKernelGGL(lq::tn_small_kernel<true>, grid3, block2, 0, st, t);
+      else hipLaunchKernelGGL(lq::tn_small_kernel<false>, grid3, block2, 0, st, t);
+      LQ_CHECK_LAUNCH("tn_small_kernel(trailing)");
+      return LQ_OK;
+    }
+    dim3 grid2((unsigned)t.ntiles);
     if (vec)
       hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, false, false, true>), grid2, block2, gemm_lds, st, t);
     else
