@@ -124,8 +124,8 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(float* __restrict__ A, 
   float* sX = sm + NB * DLD;            // 10 lower blocks of the inverse, [32][33] each
   float* sT = sX + 10 * XBLK;           // 3 temporaries, [32][33] each
   float* sLc = sT + 3 * XBLK;           // [32][32] compact copy of the current sub-block's factor
-  float* sCol = sLc + 32 * 32;          // [32] current column of the factor
-  float* sRd = sCol + 32;               // [32] reciprocals of the factor's diagonal
+  float* sCol = sLc + 32 * 32;          // [2][32] the two latest columns of the factor
+  float* sRd = sCol + 64;               // [32] reciprocals of the factor's diagonal
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float* tile = A + ((int64_t)kb * NB) * cp + (int64_t)kb * NB;
   for (int f = tid; f < NB * NB / 4; f += 256) {
@@ -143,8 +143,11 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(float* __restrict__ A, 
       float a[32];
 #pragma unroll
       for (int k = 0; k < 32; ++k) a[k] = sL[(c0 + ri) * DLD + c0 + k];
-      // Right-looking Cholesky of the 32 x 32 sub-block, row ri in this lane.  Column j of
-      // the factor goes through LDS and comes back as wave-uniform broadcast reads.
+      // Right-looking Cholesky of the 32 x 32 sub-block, row ri in this lane.  The update of
+      // the very next column takes the one value it needs through v_readlane (short
+      // dependency chain from pivot to pivot); all other columns get column j's update one
+      // step later from a copy of the column in LDS, read back as wave-uniform float4s,
+      // by which time the copy has long arrived.
 #pragma unroll
       for (int j = 0; j < 32; ++j) {
         float pj = lane_bcast(a[j], j);
@@ -153,22 +156,26 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(float* __restrict__ A, 
           if (lane == 0 && q < c && *info == 0) *info = (int32_t)(c - 1 - q) + 1;
           pj = 1.0f;
         }
-        const float dj = sqrtf(pj);
-        const float rj = 1.0f / dj;
+        float rj = __builtin_amdgcn_rsqf(pj);
+        rj = rj * fmaf(-0.5f * pj * rj, rj, 1.5f);      // one Newton step: full fp32 accuracy
+        const float dj = pj * rj;
         a[j] = (ri == j) ? dj : a[j] * rj;
+        if (lane == 0) sRd[j] = rj;
         if (j < 31) {
-          sCol[ri] = a[j];
-          if (lane == 0) sRd[j] = rj;
+          sCol[(j & 1) * 32 + ri] = a[j];
+          a[j + 1] = fmaf(-a[j], lane_bcast(a[j], j + 1), a[j + 1]);
+        }
+        if (j >= 1 && j < 31) {
+          // deferred update from column j - 1 to columns j + 1 .. 31
+          const float* cb = sCol + ((j - 1) & 1) * 32;
 #pragma unroll
           for (int k4 = (j + 1) / 4; k4 < 8; ++k4) {
-            const float4 cv = *reinterpret_cast<const float4*>(sCol + 4 * k4);
-            if (4 * k4 + 0 > j) a[4 * k4 + 0] = fmaf(-a[j], cv.x, a[4 * k4 + 0]);
-            if (4 * k4 + 1 > j) a[4 * k4 + 1] = fmaf(-a[j], cv.y, a[4 * k4 + 1]);
-            if (4 * k4 + 2 > j) a[4 * k4 + 2] = fmaf(-a[j], cv.z, a[4 * k4 + 2]);
-            if (4 * k4 + 3 > j) a[4 * k4 + 3] = fmaf(-a[j], cv.w, a[4 * k4 + 3]);
+            const float4 cv = *reinterpret_cast<const float4*>(cb + 4 * k4);
+            if (4 * k4 + 0 > j) a[4 * k4 + 0] = fmaf(-a[j - 1], cv.x, a[4 * k4 + 0]);
+            if (4 * k4 + 1 > j) a[4 * k4 + 1] = fmaf(-a[j - 1], cv.y, a[4 * k4 + 1]);
+            if (4 * k4 + 2 > j) a[4 * k4 + 2] = fmaf(-a[j - 1], cv.z, a[4 * k4 + 2]);
+            if (4 * k4 + 3 > j) a[4 * k4 + 3] = fmaf(-a[j - 1], cv.w, a[4 * k4 + 3]);
           }
-        } else if (lane == 0) {
-          sRd[j] = rj;
         }
       }
       // factor rows to LDS: the block itself and an aligned compact copy for the inverse
@@ -584,7 +591,7 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
   const int64_t cp = plan.cp;
   const int nb = plan.nb;
 
-  const size_t potrf_lds = (NB * DLD + 13 * 32 * 33 + 32 * 32 + 64) * sizeof(float);
+  const size_t potrf_lds = (NB * DLD + 13 * 32 * 33 + 32 * 32 + 96) * sizeof(float);
   static bool attr_done = false;
   if (!attr_done) {
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)potrf_diag_kernel,
