@@ -13,13 +13,18 @@
  * Conventions shared by all calls
  *   - Every pointer is a DEVICE pointer unless the comment says "host".  The
  *     caller owns every buffer; the library allocates no device memory and
- *     keeps no state between calls apart from a thread-local error string.
+ *     keeps no state between calls apart from a thread-local error string and
+ *     the side stream mentioned below.
  *   - All matrices are row-major fp32 with an explicit leading dimension
  *     counted in elements.  W is r x c with rows = output channels and
  *     columns = input channels, as in the paper (W in R^{r x c}).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; they do not synchronize.  Results are
  *     bit-identical from run to run (no atomics on floating-point data).
+ *     lq_cholesky_inv also runs part of its work on an internal side stream
+ *     (created once per host thread and device, default priority), forked from
+ *     and joined back into `stream` with events, so ordering with respect to
+ *     `stream` is unchanged.
  *   - `ws` is caller-provided scratch of at least lq_workspace_bytes() bytes,
  *     256-byte aligned, whose contents are undefined before and after a call.
  *   - Return value: LQ_OK or an error code; argument errors are found on the
@@ -60,7 +65,7 @@ typedef struct lq_params {
   int32_t group_size;      /* affine only: columns per (S, Z) group; 0 = whole row.
                               Must divide c.  Must be 0 in non-uniform mode (Section 2.1:
                               one grid per row).                                            */
-  int32_t block;           /* B, lazy-update block width; 128 is the supported value        */
+  int32_t block;           /* B, lazy-update block width: 32, 64 or 128 (paper: 128)          */
   float damp;              /* df, dampening factor (Section 2.2: 0.01)                      */
   float p;                 /* outlier-preservation strength of Eq. 5 / Eq. 7 (paper: 4)     */
   int32_t T;               /* partitions of the weight range in Eq. 7 (paper: 2048)         */
@@ -115,6 +120,7 @@ lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, float damp, fl
  *              affine:      [r x (c / group) x 2] = (S, Z) minimizing Eq. 7 over
  *                           t_min, t_max in {0..t}; Z is an integer stored as float.
  * Limits: non-uniform c <= 16384; affine group (or row when group_size = 0) <= 8192.
+ * r = 0 is a no-op (pointers are not looked at).
  */
 lq_status lq_fit_grid(const float* W, int64_t r, int64_t c, int64_t ldw, const float* hinv_diag,
                       const lq_params* P, float* grid, void* ws, size_t ws_bytes, void* stream);
@@ -130,7 +136,9 @@ lq_status lq_fit_grid(const float* W, int64_t r, int64_t c, int64_t ldw, const f
  *   codes    [r x c] uint8 out (leading dimension c): index into the ascending grid
  *            (non-uniform) or w_int of Section 2.1 (affine).
  *   row_loss [r] out or NULL: 1/2 sum_j E_kj^2, the loss errors of Eq. 3 summed per row.
- *   ws       LQ_CALL_QUANTIZE scratch (the r x B error block E).
+ *   ws       LQ_CALL_QUANTIZE scratch (error blocks E of a group of 4 column blocks, packed
+ *            diagonal blocks of U).
+ * block: 32, 64 or 128.  r = 0 is a no-op (pointers are not looked at).
  */
 lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t ldw, const float* U, int64_t ldu,
                             const float* grid, const lq_params* P, uint8_t* codes, float* row_loss,

@@ -305,6 +305,7 @@ size_t fit_grid_workspace_bytes(int64_t c) {
 extern "C" lq_status lq_fit_grid(const float* W, int64_t r, int64_t c, int64_t ldw,
                                  const float* hinv_diag, const lq_params* P, float* grid, void* ws,
                                  size_t ws_bytes, void* stream) {
+  if (r == 0 && c >= 1) return LQ_OK;   // nothing to do; empty buffers may be null
   if (!W || !hinv_diag || !grid) return lq::fail(LQ_ERR_INVALID_ARG, "lq_fit_grid: null pointer");
   if (r < 0 || c < 1 || ldw < c) return lq::fail(LQ_ERR_INVALID_ARG, "lq_fit_grid: r=%lld c=%lld ldw=%lld", (long long)r, (long long)c, (long long)ldw);
   lq_status stt = lq::check_params(P, c);

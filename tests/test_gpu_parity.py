@@ -257,3 +257,66 @@ def test_small_affine_end_to_end():
     assert ok.mean() >= 0.97
     assert agree >= 0.99
     assert abs(l_gpu / l_ref - 1.0) < 2e-3
+
+
+# ------------------------------------------------------------------ layouts and edge shapes
+def test_quantize_layer_strided_unaligned_and_empty():
+    """Leading dimensions that are not multiples of 4 (scalar load paths), a row count that
+    is not a multiple of 64, r = 0, and a ragged last block together with a ragged group of
+    blocks (c = 5 * 128 + 40)."""
+    _say("quantize strided / ragged group")
+    r, c, B, bits = 77, 5 * 128 + 40, 128, 3
+    W, H, U32, grid32 = _loop_case(r, c, 3 * c, 901, "nu", bits)
+    P = lq.lq_params_default(bits=bits, block=B)
+    Wbig = torch.zeros((r, c + 3), dtype=torch.float32, device="cuda")
+    Wbig[:, :c] = hx.to_dev(W)
+    Wv = Wbig[:, :c]                                   # ldw = c + 3
+    Ubig = torch.zeros((c, c + 1), dtype=torch.float32, device="cuda")
+    Ubig[:, :c] = hx.to_dev(U32)
+    Uv = Ubig[:, :c]                                   # ldu = c + 1
+    codes = torch.empty((r, c), dtype=torch.uint8, device="cuda")
+    row_loss = torch.empty(r, dtype=torch.float32, device="cuda")
+    ws = lq.alloc_workspace(lq.lq_workspace_bytes(lq.LQ_CALL_QUANTIZE, r, c, 0, P))
+    lq.lq_quantize_layer(Wv, Uv, hx.to_dev(grid32), P, codes, row_loss, ws)
+    lq.lq_quantize_layer(Wv[:0], Uv, hx.to_dev(grid32)[:0], P, codes[:0], None, ws)   # r = 0: no-op
+    torch.cuda.synchronize()
+    What_ref, codes_ref, loss_ref = orc.quantize_layer(W, U32, grid32, "nu", bits, B=B)
+    assert hx.code_agreement(codes.cpu().numpy(), codes_ref) >= 0.999
+    What = Wv.cpu().numpy().astype(np.float64)
+    assert abs(orc.layer_loss(W, What, H) / orc.layer_loss(W, What_ref, H) - 1.0) < 1e-3
+    assert torch.all(Wbig[:, c:] == 0) and torch.all(Ubig[:, c:] == 0)      # padding untouched
+    assert abs(row_loss.cpu().numpy().sum() / loss_ref.sum() - 1.0) < 1e-3
+
+
+def test_cholesky_and_hessian_with_padded_leading_dimensions():
+    _say("cholesky / hessian with ld > c")
+    c, n = 150, 600
+    X = _layer(c, n, 77)
+    Hbig = torch.zeros((c, c + 7), dtype=torch.float32, device="cuda")
+    Hv = Hbig[:, :c]
+    ws = lq.alloc_workspace(lq.lq_workspace_bytes(lq.LQ_CALL_HESSIAN, 0, c, n))
+    lq.lq_hessian_accumulate(Hv, hx.to_dev(X), ws)
+    Ubig = torch.full((c, c + 2), 9.0, dtype=torch.float32, device="cuda")
+    d = torch.empty(c, dtype=torch.float32, device="cuda")
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    wsc = lq.alloc_workspace(lq.lq_workspace_bytes(lq.LQ_CALL_CHOLESKY, 0, c))
+    lq.lq_cholesky_inv(Hv, 0.01, Ubig[:, :c], d, info, wsc)
+    torch.cuda.synchronize()
+    Href = orc.hessian(X)
+    assert np.max(np.abs(Hv.cpu().numpy() - Href)) < 1e-5 * np.max(np.abs(Href))
+    assert torch.all(Hbig[:, c:] == 0) and torch.all(Ubig[:, c:] == 9.0)
+    Uref, dref = orc.cholesky_inv(Hv.cpu().numpy().astype(np.float64), 0.01)
+    assert np.max(np.abs(Ubig[:, :c].cpu().numpy() - Uref) / np.sqrt(dref)[None, :]) < 2e-5
+    assert int(info.item()) == 0
+
+
+def test_results_are_bit_reproducible():
+    """No floating-point atomics anywhere: two runs of the whole pass give identical bits."""
+    _say("determinism")
+    cfg = lq_synth.CONFIGS["c1"].scaled(r=300, c=640, n_tokens=3000)
+    P = hx.params_for(cfg)
+    W = lq_synth.weights(cfg)
+    a = hx.gpu_layer_pass(W, lq_synth.activation_chunks(cfg), P)
+    b = hx.gpu_layer_pass(W, lq_synth.activation_chunks(cfg), P)
+    for k in ("H", "U", "d", "grid", "W_hat", "codes", "row_loss"):
+        assert np.array_equal(a[k], b[k]), k
