@@ -32,12 +32,17 @@ struct Acc2x2 {
   }
 };
 
+// The 128 x 128 tile is a 4 x 4 array of 32 x 32 MFMA sub-tiles; wave (wm, wn) owns the
+// sub-tiles (wm + 2 tm, wn + 2 tn).  Two sub-tiles of a wave are therefore 64 floats apart
+// in a k-major LDS row, which is what lets one ds_read2st64_b32 with immediate offsets fetch
+// both operands of a k-step: address arithmetic on the vector ALU between MFMA groups
+// (measured: about 32 idle MFMA cycles per group of four) is avoided.
 // Row (within the 128-tile) of accumulator value v of sub-tile tm for this lane.
 __device__ __forceinline__ int acc_row(int wm, int tm, int v, int lane) {
-  return wm * 64 + tm * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+  return wm * 32 + tm * 64 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
 }
 __device__ __forceinline__ int acc_col(int wn, int tn, int lane) {
-  return wn * 64 + tn * 32 + (lane & 31);
+  return wn * 32 + tn * 64 + (lane & 31);
 }
 
 // One k-chunk of KT (even) steps.  Both operands are k-major in LDS:
@@ -47,20 +52,20 @@ __device__ __forceinline__ void mma_chunk_kmajor(const float* __restrict__ sP,
                                                  const float* __restrict__ sQ, int wm, int wn,
                                                  int lane, Acc2x2& acc) {
   const int kl = lane >> 5, ml = lane & 31;
-  const float* p = sP + kl * TILE + wm * 64 + ml;   // + 2*kk*TILE per step: immediate offsets
-  const float* q = sQ + kl * TILE + wn * 64 + ml;
+  const float* p = sP + kl * TILE + wm * 32 + ml;   // + 2*kk*TILE per step: immediate offsets
+  const float* q = sQ + kl * TILE + wn * 32 + ml;
   // operands of step kk+1 are read while the MFMAs of step kk run; the scheduling
   // barriers keep the compiler from sinking the reads below the MFMAs again
   float a0[2], a1[2], b0[2], b1[2];
-  a0[0] = p[0]; a1[0] = p[32]; b0[0] = q[0]; b1[0] = q[32];
+  a0[0] = p[0]; a1[0] = p[64]; b0[0] = q[0]; b1[0] = q[64];
 #pragma unroll
   for (int kk = 0; kk < KT / 2; ++kk) {
     const int cur = kk & 1, nxt = cur ^ 1;
     if (kk + 1 < KT / 2) {
       a0[nxt] = p[2 * (kk + 1) * TILE];
-      a1[nxt] = p[2 * (kk + 1) * TILE + 32];
+      a1[nxt] = p[2 * (kk + 1) * TILE + 64];
       b0[nxt] = q[2 * (kk + 1) * TILE];
-      b1[nxt] = q[2 * (kk + 1) * TILE + 32];
+      b1[nxt] = q[2 * (kk + 1) * TILE + 64];
     }
     __builtin_amdgcn_sched_barrier(0);
     acc.t[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[cur], b0[cur], acc.t[0][0], 0, 0, 0);
@@ -113,15 +118,15 @@ __device__ __forceinline__ void mma_chunk_rowmajor_a(const float* __restrict__ s
 #pragma unroll
   for (int kk = 0; kk < RM_KT / 2; ++kk) {
     const int k = 2 * kk + kl;
-    float a0 = sA[(wm * 64 + ml) * RM_LD + k];
-    float a1 = sA[(wm * 64 + 32 + ml) * RM_LD + k];
+    float a0 = sA[(wm * 32 + ml) * RM_LD + k];
+    float a1 = sA[(wm * 32 + 64 + ml) * RM_LD + k];
     float b0, b1;
     if (B_KMAJOR) {
-      b0 = sB[k * TILE + wn * 64 + ml];
-      b1 = sB[k * TILE + wn * 64 + 32 + ml];
+      b0 = sB[k * TILE + wn * 32 + ml];
+      b1 = sB[k * TILE + wn * 32 + 64 + ml];
     } else {
-      b0 = sB[(wn * 64 + ml) * RM_LD + k];
-      b1 = sB[(wn * 64 + 32 + ml) * RM_LD + k];
+      b0 = sB[(wn * 32 + ml) * RM_LD + k];
+      b1 = sB[(wn * 32 + 64 + ml) * RM_LD + k];
     }
     acc.t[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc.t[0][0], 0, 0, 0);
     acc.t[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc.t[0][1], 0, 0, 0);

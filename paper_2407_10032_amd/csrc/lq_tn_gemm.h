@@ -151,16 +151,17 @@ __device__ __forceinline__ void tn_store_chunk(float* __restrict__ s, const Chun
   }
 }
 
-// The k loop of one tile: global loads of stage s+1 are issued before the MFMAs of stage s
-// and stored to the other LDS buffer after them.
-template <int KT, bool VEC, bool FAST>
-__device__ __forceinline__ void tn_mainloop(const TnGemmArgs& a, float* smem, int64_t kbeg,
-                                            int64_t kend, int64_t m0, int64_t n0, bool diag, int wm,
-                                            int wn, int lane, int tid, Acc2x2& acc) {
+// The k loop of one tile, guarded variant (edge tiles, unaligned operands, ragged slices):
+// global loads of stage s+1 are issued before the MFMAs of stage s and stored to the other
+// LDS buffer after them.
+template <int KT, bool VEC>
+__device__ __forceinline__ void tn_mainloop_safe(const TnGemmArgs& a, float* smem, int64_t kbeg,
+                                                 int64_t kend, int64_t m0, int64_t n0, bool diag,
+                                                 int wm, int wn, int lane, int tid, Acc2x2& acc) {
   constexpr int STAGE = KT * TILE;
-  ChunkRegs<KT> rp = tn_load_chunk<KT, VEC, FAST>(a.P, a.ldp, kbeg, kend, m0, a.M, tid);
+  ChunkRegs<KT> rp = tn_load_chunk<KT, VEC, false>(a.P, a.ldp, kbeg, kend, m0, a.M, tid);
   ChunkRegs<KT> rq = rp;
-  if (!diag) rq = tn_load_chunk<KT, VEC, FAST>(a.Q, a.ldq, kbeg, kend, n0, a.N, tid);
+  if (!diag) rq = tn_load_chunk<KT, VEC, false>(a.Q, a.ldq, kbeg, kend, n0, a.N, tid);
   tn_store_chunk<KT>(smem, rp, tid);
   if (!diag) tn_store_chunk<KT>(smem + 2 * STAGE, rq, tid);
   __syncthreads();
@@ -168,8 +169,8 @@ __device__ __forceinline__ void tn_mainloop(const TnGemmArgs& a, float* smem, in
   for (int64_t k0 = kbeg; k0 < kend; k0 += KT) {
     const bool more = (k0 + KT) < kend;
     if (more) {
-      rp = tn_load_chunk<KT, VEC, FAST>(a.P, a.ldp, k0 + KT, kend, m0, a.M, tid);
-      if (!diag) rq = tn_load_chunk<KT, VEC, FAST>(a.Q, a.ldq, k0 + KT, kend, n0, a.N, tid);
+      rp = tn_load_chunk<KT, VEC, false>(a.P, a.ldp, k0 + KT, kend, m0, a.M, tid);
+      if (!diag) rq = tn_load_chunk<KT, VEC, false>(a.Q, a.ldq, k0 + KT, kend, n0, a.N, tid);
     }
     const float* cp = smem + buf * STAGE;
     mma_chunk_kmajor<KT>(cp, diag ? cp : cp + 2 * STAGE, wm, wn, lane, acc);
@@ -181,6 +182,176 @@ __device__ __forceinline__ void tn_mainloop(const TnGemmArgs& a, float* smem, in
     __syncthreads();
     buf ^= 1;
   }
+}
+
+struct TnOperands { float a0[2], a1[2], b0[2], b1[2]; };
+
+// Addresses one thread uses in one LDS buffer of the fast loop: where its wave reads the
+// A and B operands of k-step 0 and where the thread stores its part of a stage (P operand;
+// the Q operand sits 2 * KT * TILE floats further).
+struct TnLdsAddr { const float* p; const float* q; float* st; };
+
+// Global source of one operand for the fast loop: a wave-uniform row base (kept in scalar
+// registers) plus this thread's byte offsets of its KT / 8 rows, so that a stage's loads
+// need no vector-ALU address arithmetic.
+template <int KT> struct TnFastSrc {
+  typedef const __attribute__((address_space(1))) char* GlobalBytes;   // global_load, not flat_load
+  typedef float Vec4 __attribute__((ext_vector_type(4)));
+  typedef const __attribute__((address_space(1))) Vec4* GlobalVec4;
+  GlobalBytes base;
+  unsigned off[KT / 8];
+  int64_t step;                                  // bytes per stage
+  __device__ __forceinline__ void init(const float* src, int64_t ld, int64_t k0, int64_t col0, int tid) {
+    const uint64_t v = reinterpret_cast<uint64_t>(src + k0 * ld + col0);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    base = (GlobalBytes)(((uint64_t)hi << 32) | lo);
+#pragma unroll
+    for (int i = 0; i < KT / 8; ++i)
+      off[i] = (unsigned)(((tid >> 5) + 8 * i) * (int)ld + 4 * (tid & 31)) * 4u;
+    step = (int64_t)KT * ld * 4;
+  }
+  // The empty asm keeps the 32-bit offset opaque at the point of use, so that its zero
+  // extension is not hoisted out of the loop and instruction selection sees
+  // "scalar base + 32-bit vector offset" (global_load with an SGPR base, no 64-bit add).
+  __device__ __forceinline__ Vec4 load_one(int i) const {
+    unsigned o = off[i];
+    asm volatile("" : "+v"(o));
+    return *(GlobalVec4)(base + o);
+  }
+  __device__ __forceinline__ ChunkRegs<KT> load() const {
+    ChunkRegs<KT> c;
+    const Vec4 v0 = load_one(0);
+    const Vec4 v1 = load_one(1);
+    c.r0 = make_float4(v0.x, v0.y, v0.z, v0.w);
+    c.r1 = make_float4(v1.x, v1.y, v1.z, v1.w);
+    if constexpr (KT == 32) {
+      const Vec4 v2 = load_one(2);
+      const Vec4 v3 = load_one(3);
+      c.r2 = make_float4(v2.x, v2.y, v2.z, v2.w);
+      c.r3 = make_float4(v3.x, v3.y, v3.z, v3.w);
+    }
+    return c;
+  }
+  __device__ __forceinline__ void next() { base += step; }
+};
+
+template <int KT>
+__device__ __forceinline__ void tn_store_chunk_at(float* __restrict__ d, const ChunkRegs<KT>& c) {
+  *reinterpret_cast<float4*>(d) = c.r0;
+  *reinterpret_cast<float4*>(d + 8 * TILE) = c.r1;
+  if constexpr (KT == 32) {
+    *reinterpret_cast<float4*>(d + 16 * TILE) = c.r2;
+    *reinterpret_cast<float4*>(d + 24 * TILE) = c.r3;
+  }
+}
+
+// One k stage of tn_mainloop_fast over buffer `cur`.  On entry o.*[0] holds the operands
+// of k-step 0 of this stage; if MORE, on exit it holds those of k-step 0 of the next
+// stage, whose data (rp, rq) this stage stores to buffer `nxt`.
+template <int KT, bool MORE, bool DIAG>
+__device__ __forceinline__ void tn_fast_stage(const TnLdsAddr& cur, const TnLdsAddr& nxt,
+                                              const ChunkRegs<KT>& rp, const ChunkRegs<KT>& rq,
+                                              TnOperands& o, Acc2x2& acc) {
+  constexpr int STAGE = KT * TILE;
+  constexpr int STEPS = KT / 2;
+  constexpr int STORE_AT = STEPS - 4;     // k-step before whose MFMAs the next stage is stored
+  static_assert(STEPS % 2 == 0 && STORE_AT >= 0, "operand slots alternate per k-step");
+  const float* p = cur.p;
+  const float* q = cur.q;
+#pragma unroll
+  for (int kk = 0; kk < STEPS; ++kk) {
+    const int c = kk & 1, n = c ^ 1;
+    if (kk + 1 < STEPS) {
+      o.a0[n] = p[2 * (kk + 1) * TILE];
+      o.a1[n] = p[2 * (kk + 1) * TILE + 64];
+      o.b0[n] = q[2 * (kk + 1) * TILE];
+      o.b1[n] = q[2 * (kk + 1) * TILE + 64];
+    }
+    if (MORE && kk == STORE_AT) {
+      tn_store_chunk_at<KT>(nxt.st, rp);
+      if (!DIAG) tn_store_chunk_at<KT>(nxt.st + 2 * STAGE, rq);
+    }
+    if (MORE && kk == STEPS - 1) {
+      __syncthreads();                       // stores landed, every read of this buffer issued
+      o.a0[n] = nxt.p[0]; o.a1[n] = nxt.p[64];
+      o.b0[n] = nxt.q[0]; o.b1[n] = nxt.q[64];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    acc.t[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a0[c], o.b0[c], acc.t[0][0], 0, 0, 0);
+    acc.t[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a0[c], o.b1[c], acc.t[0][1], 0, 0, 0);
+    acc.t[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a1[c], o.b0[c], acc.t[1][0], 0, 0, 0);
+    acc.t[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a1[c], o.b1[c], acc.t[1][1], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// The k loop of an interior tile (no predicates), written so that the MFMA pipe is the
+// only vector unit the steady state uses:
+//   * global loads of stage s+1 are issued at the top of stage s from a scalar base plus
+//     fixed per-thread offsets;
+//   * their LDS stores (into the buffer not being read) are issued a few k-steps before
+//     the end of stage s, between MFMA groups;
+//   * the barrier sits before the LAST MFMA group of the stage, whose operands are
+//     already in registers; the first operands of stage s+1 are read right after it;
+//   * all LDS addresses of both buffers are computed once, and the loop is unrolled over
+//     the two buffers, so that a stage has no vector-ALU instruction at all: a VALU
+//     instruction between MFMAs was measured to idle the MFMA pipe for about 16 cycles.
+// Scheduling barriers pin the order.  nst = number of stages (>= 1), wave-uniform.
+template <int KT, bool DIAG>
+__device__ __forceinline__ void tn_fast_loop(TnFastSrc<KT>& sp, TnFastSrc<KT>& sq, int nst,
+                                             const TnLdsAddr& b0, const TnLdsAddr& b1,
+                                             ChunkRegs<KT>& rp, ChunkRegs<KT>& rq, TnOperands& o,
+                                             Acc2x2& acc) {
+  int left = nst - 1;                            // stages that are followed by another
+  while (left >= 2) {
+    sp.next(); rp = sp.load();
+    if (!DIAG) { sq.next(); rq = sq.load(); }
+    tn_fast_stage<KT, true, DIAG>(b0, b1, rp, rq, o, acc);
+    sp.next(); rp = sp.load();
+    if (!DIAG) { sq.next(); rq = sq.load(); }
+    tn_fast_stage<KT, true, DIAG>(b1, b0, rp, rq, o, acc);
+    left -= 2;
+  }
+  if (left) {
+    sp.next(); rp = sp.load();
+    if (!DIAG) { sq.next(); rq = sq.load(); }
+    tn_fast_stage<KT, true, DIAG>(b0, b1, rp, rq, o, acc);
+    tn_fast_stage<KT, false, DIAG>(b1, b1, rp, rq, o, acc);
+  } else {
+    tn_fast_stage<KT, false, DIAG>(b0, b0, rp, rq, o, acc);
+  }
+}
+
+template <int KT, bool VEC>
+__device__ __forceinline__ void tn_mainloop_fast(const TnGemmArgs& a, float* smem, int64_t kbeg,
+                                                 int64_t kend, int64_t m0, int64_t n0, bool diag,
+                                                 int wm, int wn, int lane, int tid, Acc2x2& acc) {
+  constexpr int STAGE = KT * TILE;
+  const int kl = lane >> 5, ml = lane & 31;
+  const int offp = kl * TILE + wm * 32 + ml;
+  const int offq = (diag ? 0 : 2 * STAGE) + kl * TILE + wn * 32 + ml;
+  const int offs = (tid >> 5) * TILE + 4 * (tid & 31);
+  TnLdsAddr b0, b1;
+  b0.p = smem + offp;         b0.q = smem + offq;         b0.st = smem + offs;
+  b1.p = smem + STAGE + offp; b1.q = smem + STAGE + offq; b1.st = smem + STAGE + offs;
+  const int nst = __builtin_amdgcn_readfirstlane((int)((kend - kbeg) / KT));
+
+  TnFastSrc<KT> sp, sq;
+  sp.init(a.P, a.ldp, kbeg, m0, tid);
+  sq.init(a.Q, a.ldq, kbeg, n0, tid);
+  ChunkRegs<KT> rp = sp.load();
+  ChunkRegs<KT> rq = rp;
+  if (!diag) rq = sq.load();
+  tn_store_chunk_at<KT>(b0.st, rp);
+  if (!diag) tn_store_chunk_at<KT>(b0.st + 2 * STAGE, rq);
+  __syncthreads();
+
+  TnOperands o;
+  o.a0[0] = b0.p[0]; o.a1[0] = b0.p[64];
+  o.b0[0] = b0.q[0]; o.b1[0] = b0.q[64];
+  if (diag) tn_fast_loop<KT, true>(sp, sq, nst, b0, b1, rp, rq, o, acc);
+  else tn_fast_loop<KT, false>(sp, sq, nst, b0, b1, rp, rq, o, acc);
 }
 
 template <int KT, bool SYM, bool PARTIAL, bool VEC, int MINW = 2>
@@ -207,9 +378,10 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void tn_gemm_kernel(TnGemmArgs a)
   if (kbeg < kend) {
     // interior tiles of an aligned operand whose slice is a whole number of stages take the
     // predicate-free loads; the two loops are separate so that each has one load variant
-    const bool fast = VEC && (m0 + TILE <= a.M) && (n0 + TILE <= a.N) && ((kend - kbeg) % KT == 0);
-    if (fast) tn_mainloop<KT, VEC, true>(a, smem, kbeg, kend, m0, n0, diag, wm, wn, lane, tid, acc);
-    else tn_mainloop<KT, VEC, false>(a, smem, kbeg, kend, m0, n0, diag, wm, wn, lane, tid, acc);
+    const bool fast = VEC && (m0 + TILE <= a.M) && (n0 + TILE <= a.N) && ((kend - kbeg) % KT == 0) &&
+                      a.ldp < (1 << 24) && a.ldq < (1 << 24);   // 32-bit byte offsets inside a stage
+    if (fast) tn_mainloop_fast<KT, VEC>(a, smem, kbeg, kend, m0, n0, diag, wm, wn, lane, tid, acc);
+    else tn_mainloop_safe<KT, VEC>(a, smem, kbeg, kend, m0, n0, diag, wm, wn, lane, tid, acc);
   }
 
   if (PARTIAL) {
