@@ -171,7 +171,9 @@ def main():
                    % (cfg.name, r, c, n, c, cfg.bits, "non-uniform" if cfg.mode == "nu" else "affine g%d" % cfg.group_size,
                       cfg.block, cfg.damp, cfg.p),
                    "stage_ms": {"hessian": stage_ms[0], "cholesky_inv": stage_ms[1], "fit_grid": stage_ms[2],
-                                "quantize_layer": stage_ms[3]}},
+                                "quantize_layer": stage_ms[3]},
+                   # the same pass when H is reused from a projection with the same input
+                   "weights_per_s_without_hessian": r * c / (float(stage_ms[1:].sum()) * 1e-3)},
         "roofline": {"bound": "mfma", "kernel": "tn_gemm_kernel (H += 2 X^T X, upper tiles) + partial-sum reduce",
                      "achieved": achieved, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / FP32_MFMA_PEAK_TFLOPS,

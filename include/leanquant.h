@@ -132,7 +132,7 @@ lq_status lq_fit_grid(const float* W, int64_t r, int64_t c, int64_t ldw, const f
  *   W        [r x c] (ldw) in/out: the working copy; on return it holds W_hat,
  *            the dequantized result Algorithm 1 returns.
  *   U        [c x c] (ldu) from lq_cholesky_inv, read only.
- *   grid     as written by lq_fit_grid for the same P.
+ *   grid     as written by lq_fit_grid for the same P; 16-byte aligned.
  *   codes    [r x c] uint8 out (leading dimension c): index into the ascending grid
  *            (non-uniform) or w_int of Section 2.1 (affine).
  *   row_loss [r] out or NULL: 1/2 sum_j E_kj^2, the loss errors of Eq. 3 summed per row.

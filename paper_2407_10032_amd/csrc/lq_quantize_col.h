@@ -54,28 +54,36 @@ template <> struct GridVec<8> { typedef f8v type; };
 template <> struct GridVec<16> { typedef f16v type; };
 
 // g: the K grid points; m: the K - 1 midpoints in elements 0..K-2 (element K-1 unused).
-__device__ __forceinline__ void quant_nu_vec(float w, f2v g, f2v m, float& q, int& code) {
+// The code is built most significant bit first as code = 2 * code + bit in a vector
+// register at each level; the empty asm at the end keeps the compiler from holding the
+// comparison masks of a whole sub-block in scalar registers (and spilling them) until the
+// codes are stored.
+__device__ __forceinline__ void quant_nu_bits(float w, f2v g, f2v m, float& q, int& code) {
   const bool up = w > m.x;
   q = up ? g.y : g.x;
-  code = up ? 1 : 0;
+  code = 2 * code + (up ? 1 : 0);
 }
-__device__ __forceinline__ void quant_nu_vec(float w, f4v g, f4v m, float& q, int& code) {
+__device__ __forceinline__ void quant_nu_bits(float w, f4v g, f4v m, float& q, int& code) {
   const bool up = w > m.y;
-  int c;
-  quant_nu_vec(w, up ? g.hi : g.lo, up ? m.hi : m.lo, q, c);
-  code = c + (up ? 2 : 0);
+  code = 2 * code + (up ? 1 : 0);
+  quant_nu_bits(w, up ? g.hi : g.lo, up ? m.hi : m.lo, q, code);
 }
-__device__ __forceinline__ void quant_nu_vec(float w, f8v g, f8v m, float& q, int& code) {
+__device__ __forceinline__ void quant_nu_bits(float w, f8v g, f8v m, float& q, int& code) {
   const bool up = w > m.s3;
-  int c;
-  quant_nu_vec(w, up ? g.hi : g.lo, up ? m.hi : m.lo, q, c);
-  code = c + (up ? 4 : 0);
+  code = 2 * code + (up ? 1 : 0);
+  quant_nu_bits(w, up ? g.hi : g.lo, up ? m.hi : m.lo, q, code);
 }
-__device__ __forceinline__ void quant_nu_vec(float w, f16v g, f16v m, float& q, int& code) {
+__device__ __forceinline__ void quant_nu_bits(float w, f16v g, f16v m, float& q, int& code) {
   const bool up = w > m.s7;
-  int c;
-  quant_nu_vec(w, up ? g.hi : g.lo, up ? m.hi : m.lo, q, c);
-  code = c + (up ? 8 : 0);
+  code = 2 * code + (up ? 1 : 0);
+  quant_nu_bits(w, up ? g.hi : g.lo, up ? m.hi : m.lo, q, code);
+}
+template <typename V>
+__device__ __forceinline__ void quant_nu_vec(float w, V g, V m, float& q, int& code) {
+  int c = 0;
+  quant_nu_bits(w, g, m, q, c);
+  asm volatile("" : "+v"(c));
+  code = c;
 }
 
 template <int B, int BITS, bool AFF>
@@ -108,8 +116,23 @@ __global__ __launch_bounds__(QT) void column_block_kernel(ColArgs a, const float
   // the row's grid first (its loads overlap the block load below)
   typename GridVec<K>::type g, mid;
   float S = 1.0f, Z = 0.0f, invS = 1.0f;
+  if (!AFF) {
+    // rows past r read row 0's grid (their results are never stored)
+    const float* grow = a.grid + (valid ? row : 0) * K;
+    if constexpr (K >= 4) {
 #pragma unroll
-  for (int m = 0; m < K; ++m) g[m] = (!AFF && valid) ? a.grid[row * K + m] : 0.0f;
+      for (int m4 = 0; m4 < K / 4; ++m4) {
+        const float4 v = reinterpret_cast<const float4*>(grow)[m4];
+        g[4 * m4 + 0] = v.x; g[4 * m4 + 1] = v.y; g[4 * m4 + 2] = v.z; g[4 * m4 + 3] = v.w;
+      }
+    } else {
+#pragma unroll
+      for (int m = 0; m < K; ++m) g[m] = grow[m];
+    }
+  } else {
+#pragma unroll
+    for (int m = 0; m < K; ++m) g[m] = 0.0f;
+  }
 
   // this wavefront's 64 x B piece of W -> LDS (rows past r and columns past c read as zero);
   // eight 16-byte loads are in flight before their values are written to LDS

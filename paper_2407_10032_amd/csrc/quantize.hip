@@ -69,6 +69,7 @@ extern "C" lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t l
                                        void* stream) {
   if (r == 0 && c >= 1) return LQ_OK;   // nothing to do; empty buffers may be null
   if (!W || !U || !grid || !codes) return lq::fail(LQ_ERR_INVALID_ARG, "lq_quantize_layer: null pointer");
+  if (!lq::aligned(grid, 16)) return lq::fail(LQ_ERR_INVALID_ARG, "lq_quantize_layer: grid must be 16-byte aligned");
   if (r < 0 || c < 1 || ldw < c || ldu < c)
     return lq::fail(LQ_ERR_INVALID_ARG, "lq_quantize_layer: r=%lld c=%lld ldw=%lld ldu=%lld", (long long)r, (long long)c, (long long)ldw, (long long)ldu);
   lq_status stt = lq::check_params(P, c);
