@@ -108,33 +108,116 @@ constexpr int XLD = 33;                 // leading dimension of a 32 x 32 block 
 constexpr int XBLK = 32 * XLD;
 __device__ __forceinline__ int xblk(int i, int k) { return (i * (i + 1) / 2 + k) * XBLK; }
 
+// One right-looking substitution step on a lane's 32 values, shared by the row solve
+// (x L^T = a) and the inverse of a sub-block's factor: the column `step` of the factor
+// arrives in `cur` (broadcast float4 pieces), column step + 1 is fetched into `nxt`
+// meanwhile.  SOLVE: x[step] *= rd, x[k] -= x[step] L[k][step].  Otherwise (inverse,
+// lane = column ri): x[step] = (delta - x[step]) * rd, x[k] += L[k][step] x[step].
+// The empty asm pins the updates to this step; otherwise they are sunk to their last use
+// and every prefetched column stays live.
+template <int STEP, bool SOLVE>
+__device__ __forceinline__ void subst_step(float (&x)[32], const float4 (&cur)[8], float4 (&nxt)[8],
+                                           const float* lt, const float* rd, float& rdn, int ri) {
+  const float rdi = rdn;
+  if (STEP + 1 < 32) {
+    rdn = rd[STEP + 1];
+#pragma unroll
+    for (int k4 = (STEP + 2) / 4; k4 < 8; ++k4)
+      nxt[k4] = *reinterpret_cast<const float4*>(lt + (STEP + 1) * 32 + 4 * k4);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  if (SOLVE) x[STEP] *= rdi;
+  else x[STEP] = ((ri == STEP) ? 1.0f : -x[STEP]) * rdi;
+  const float xs = SOLVE ? -x[STEP] : x[STEP];
+#pragma unroll
+  for (int k4 = (STEP + 1) / 4; k4 < 8; ++k4) {
+    const float4 lv = cur[k4];
+    if (4 * k4 + 0 > STEP) x[4 * k4 + 0] = fmaf(xs, lv.x, x[4 * k4 + 0]);
+    if (4 * k4 + 1 > STEP) x[4 * k4 + 1] = fmaf(xs, lv.y, x[4 * k4 + 1]);
+    if (4 * k4 + 2 > STEP) x[4 * k4 + 2] = fmaf(xs, lv.z, x[4 * k4 + 2]);
+    if (4 * k4 + 3 > STEP) x[4 * k4 + 3] = fmaf(xs, lv.w, x[4 * k4 + 3]);
+  }
+#pragma unroll
+  for (int k = STEP + 1; k < 32; ++k) asm volatile("" : "+v"(x[k]));
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int STEP, bool SOLVE>
+__device__ __forceinline__ void subst_steps(float (&x)[32], float4 (&ca)[8], float4 (&cb)[8],
+                                            const float* lt, const float* rd, float& rdn, int ri) {
+  if constexpr (STEP < 32) {
+    subst_step<STEP, SOLVE>(x, ca, cb, lt, rd, rdn, ri);
+    subst_step<STEP + 1, SOLVE>(x, cb, ca, lt, rd, rdn, ri);
+    subst_steps<STEP + 2, SOLVE>(x, ca, cb, lt, rd, rdn, ri);
+  }
+}
+
+// x: the lane's 32 values (SOLVE: a row of the sub-panel; otherwise zeros on entry, a
+// column of the inverse on exit); lt: the factor column-major, [32][32]; rd: 1 / diagonal.
+template <bool SOLVE>
+__device__ __forceinline__ void substitute32(float (&x)[32], const float* lt, const float* rd, int ri) {
+  float4 ca[8], cb[8];
+  float rdn = rd[0];
+#pragma unroll
+  for (int k4 = 0; k4 < 8; ++k4) {
+    ca[k4] = *reinterpret_cast<const float4*>(lt + 4 * k4);
+    cb[k4] = ca[k4];
+  }
+  subst_steps<0, SOLVE>(x, ca, cb, lt, rd, rdn, ri);
+}
+
 // Factor the 128 x 128 diagonal block kb and invert its factor, all in LDS, one
 // workgroup.  The block is processed as 4 sub-panels of 32 columns: wavefront 0
-// factors and inverts the 32 x 32 diagonal sub-block in registers (lane = row for the
-// factor, lane = column for the inverse; entries of other lanes come through
-// v_readlane), the sub-panel below it and the rest of the block are then updated with
-// 32 x 32 MFMA tiles.  The inverse of the whole factor is assembled block by block
-// from the inverted diagonal sub-blocks: X_ik = -X_ii * sum_{k<=m<i} L_im X_mk.
+// factors the 32 x 32 diagonal sub-block in registers (lane = row; entries of other
+// lanes come through v_readlane), the rows below it are solved against the sub-block by
+// forward substitution (one row per lane, the factor read as broadcast values), and the
+// rest of the block is updated with 32 x 32 MFMA tiles.  The inverse of a sub-block's
+// factor (lane = column) is not needed by these steps; wavefront 3 computes it while
+// wavefront 0 factors the next sub-block.  The inverse of the whole factor is then
+// assembled block by block: X_ik = -X_ii * sum_{k<=m<i} L_im X_mk.
 // Writes L_kk back (upper part zeroed) and its inverse to Dinv[kb] (128 x 128, ld 128).
-__global__ __launch_bounds__(256) void potrf_diag_kernel(float* __restrict__ A, int64_t cp, int kb,
+__global__ __launch_bounds__(256, 1) void potrf_diag_kernel(float* __restrict__ A, int64_t cp, int kb,
                                                          float* __restrict__ Dinv,
                                                          int32_t* __restrict__ info, int64_t c) {
   extern __shared__ __align__(16) float sm[];
   float* sL = sm;                       // [128][129]
   float* sX = sm + NB * DLD;            // 10 lower blocks of the inverse, [32][33] each
   float* sT = sX + 10 * XBLK;           // 3 temporaries, [32][33] each
-  float* sLc = sT + 3 * XBLK;           // [32][32] compact copy of the current sub-block's factor
-  float* sCol = sLc + 32 * 32;          // [2][32] the two latest columns of the factor
-  float* sRd = sCol + 64;               // [32] reciprocals of the factor's diagonal
+  float* sLt = sT + 3 * XBLK;           // [4][32][32] column-major copies of the sub-blocks' factors
+  float* sCol = sLt + 4 * 32 * 32;      // [2][32] the two latest columns of the factor
+  float* sRd = sCol + 64;               // [4][32] reciprocals of the factors' diagonals
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float* tile = A + ((int64_t)kb * NB) * cp + (int64_t)kb * NB;
-  for (int f = tid; f < NB * NB / 4; f += 256) {
-    int row = f >> 5, c4 = f & 31;
-    float4 v = *reinterpret_cast<const float4*>(tile + (int64_t)row * cp + 4 * c4);
-    float* d = sL + row * DLD + 4 * c4;
-    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+  {
+    // all sixteen 16-byte loads of a thread are in flight before the first LDS store
+    float4 v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int f = tid + u * 256;
+      v[u] = *reinterpret_cast<const float4*>(tile + (int64_t)(f >> 5) * cp + 4 * (f & 31));
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int f = tid + u * 256;
+      float* d = sL + (f >> 5) * DLD + 4 * (f & 31);
+      d[0] = v[u].x; d[1] = v[u].y; d[2] = v[u].z; d[3] = v[u].w;
+    }
   }
   __syncthreads();
+
+  // inverse of sub-block q's factor, column ri in each of 32 lanes (right-looking
+  // substitution on the unit vector e_ri)
+  auto invert_subblock = [&](int q) {
+    const int ri = lane & 31;
+    float x[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) x[i] = 0.0f;
+    substitute32<false>(x, sLt + q * 1024, sRd + q * 32, ri);
+    if (lane < 32) {
+#pragma unroll
+      for (int k = 0; k < 32; ++k) sX[xblk(q, q) + k * XLD + ri] = (k >= ri) ? x[k] : 0.0f;
+    }
+  };
 
   for (int kk = 0; kk < 4; ++kk) {
     const int c0 = kk * 32;
@@ -160,7 +243,7 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(float* __restrict__ A, 
         rj = rj * fmaf(-0.5f * pj * rj, rj, 1.5f);      // one Newton step: full fp32 accuracy
         const float dj = pj * rj;
         a[j] = (ri == j) ? dj : a[j] * rj;
-        if (lane == 0) sRd[j] = rj;
+        if (lane == 0) sRd[kk * 32 + j] = rj;
         if (j < 31) {
           sCol[(j & 1) * 32 + ri] = a[j];
           a[j + 1] = fmaf(-a[j], lane_bcast(a[j], j + 1), a[j + 1]);
@@ -178,46 +261,34 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(float* __restrict__ A, 
           }
         }
       }
-      // factor rows to LDS: the block itself and an aligned compact copy for the inverse
+      // factor rows to LDS: the block itself and an aligned column-major copy for the solves
       if (lane < 32) {
+        float* lt = sLt + kk * 1024;
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
           if (k <= ri) sL[(c0 + ri) * DLD + c0 + k] = a[k];
-          sLc[ri * 32 + k] = (k <= ri) ? a[k] : 0.0f;
+          lt[k * 32 + ri] = (k <= ri) ? a[k] : 0.0f;
         }
       }
-      // inverse of the sub-block's factor, column ri in this lane: row i of the factor is
-      // read as broadcast float4s, x[i] = (delta_i,ri - sum_k L[i][k] x[k]) / L[i][i]
-      float x[32];
-#pragma unroll
-      for (int i = 0; i < 32; ++i) {
-        float acc0 = 0.0f, acc1 = 0.0f;
-#pragma unroll
-        for (int k4 = 0; k4 < (i + 3) / 4; ++k4) {
-          const float4 lv = *reinterpret_cast<const float4*>(sLc + i * 32 + 4 * k4);
-          if (4 * k4 + 0 < i) acc0 = fmaf(lv.x, x[4 * k4 + 0], acc0);
-          if (4 * k4 + 1 < i) acc1 = fmaf(lv.y, x[4 * k4 + 1], acc1);
-          if (4 * k4 + 2 < i) acc0 = fmaf(lv.z, x[4 * k4 + 2], acc0);
-          if (4 * k4 + 3 < i) acc1 = fmaf(lv.w, x[4 * k4 + 3], acc1);
-        }
-        x[i] = ((ri == i) ? 1.0f : -(acc0 + acc1)) * sRd[i];
-      }
-      if (lane < 32) {
-#pragma unroll
-        for (int k = 0; k < 32; ++k) sX[xblk(kk, kk) + k * XLD + ri] = (k >= ri) ? x[k] : 0.0f;
-      }
+    } else if (wave == 3 && kk > 0) {
+      // the previous sub-block's inverse is only needed for the assembly at the end: it is
+      // computed here, next to the factorization, instead of between factorization and solve
+      invert_subblock(kk - 1);
     }
     __syncthreads();
-    // sub-panel: A[ib, kk] <- A[ib, kk] * inv(L_kk)^T for the 32-row blocks below
+    // sub-panel: rows below the sub-block, one row per lane (wavefronts 0 and 1):
+    // x L_kk^T = a by substitution, right-looking: x[j] /= L[j][j], then
+    // x[k] -= x[j] L[k][j] for k > j with column j of the factor as broadcast float4s
     {
-      const int ib = kk + 1 + wave;
-      if (ib < 4) {
-        lq::floatx16 acc;
+      const int rrow = c0 + 32 + wave * 64 + lane;
+      if (wave < 2 && rrow < NB) {
+        float* arow = sL + rrow * DLD + c0;
+        float x[32];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-        float* blk = sL + (ib * 32) * DLD + c0;
-        tile32_mma<true, false>(acc, blk, DLD, sX + xblk(kk, kk), XLD, lane);
-        tile32_store(acc, blk, DLD, lane, 1.0f);
+        for (int k = 0; k < 32; ++k) x[k] = arow[k];
+        substitute32<true>(x, sLt + kk * 1024, sRd + kk * 32, 0);
+#pragma unroll
+        for (int k = 0; k < 32; ++k) arow[k] = x[k];
       }
     }
     __syncthreads();
@@ -238,6 +309,8 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(float* __restrict__ A, 
     }
     __syncthreads();
   }
+  if (wave == 3) invert_subblock(3);
+  __syncthreads();
 
   // inverse of the 128 x 128 factor from the inverted diagonal sub-blocks
   for (int dist = 1; dist < 4; ++dist) {
@@ -352,16 +425,28 @@ __global__ __launch_bounds__(WG_THREADS, 2) void chol_gemm_kernel(ChArgs a) {
     __syncthreads();
   }
 
+  // all loads of the old values are issued before the first store (a load after a store to
+  // a possibly aliasing address would wait for it)
+  if (SUBTRACT) {
+#pragma unroll
+    for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < 2; ++tn) {
+        float old[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          old[v] = Out[(int64_t)lq::acc_row(wm, tm, v, lane) * ldo + lq::acc_col(wn, tn, lane)];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc.t[tm][tn][v] = old[v] - acc.t[tm][tn][v];
+      }
+  }
 #pragma unroll
   for (int tm = 0; tm < 2; ++tm)
 #pragma unroll
     for (int tn = 0; tn < 2; ++tn)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float* o = Out + (int64_t)lq::acc_row(wm, tm, v, lane) * ldo + lq::acc_col(wn, tn, lane);
-        if (SUBTRACT) *o -= acc.t[tm][tn][v];
-        else *o = acc.t[tm][tn][v];
-      }
+      for (int v = 0; v < 16; ++v)
+        Out[(int64_t)lq::acc_row(wm, tm, v, lane) * ldo + lq::acc_col(wn, tn, lane)] = acc.t[tm][tn][v];
 }
 
 // The same four products cut into smaller output tiles, for steps that have too few
@@ -591,7 +676,7 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
   const int64_t cp = plan.cp;
   const int nb = plan.nb;
 
-  const size_t potrf_lds = (NB * DLD + 13 * 32 * 33 + 32 * 32 + 96) * sizeof(float);
+  const size_t potrf_lds = (NB * DLD + 13 * 32 * 33 + 4 * 32 * 32 + 64 + 128) * sizeof(float);
   static bool attr_done = false;
   if (!attr_done) {
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)potrf_diag_kernel,

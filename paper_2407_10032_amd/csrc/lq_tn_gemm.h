@@ -393,6 +393,39 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void tn_gemm_kernel(TnGemmArgs a)
 #pragma unroll
         for (int v = 0; v < 16; ++v)
           out[acc_row(wm, tm, v, lane) * TILE + acc_col(wn, tn, lane)] = acc.t[tm][tn][v];
+  } else if (!SYM && VEC && (m0 + TILE <= a.M) && (n0 + TILE <= a.N) && (a.ldc % 4 == 0) &&
+             ((reinterpret_cast<uintptr_t>(a.C) & 15) == 0) && (n0 % 4 == 0)) {
+    // Interior tile of a 16-byte aligned C: the accumulators go through LDS so that every
+    // thread reads, updates and writes whole 16-byte pieces of C rows, with all of its
+    // sixteen loads in flight before the first add (element-wise read-modify-write from
+    // the accumulator layout is serialized by the possible aliasing of its own stores).
+    __syncthreads();                               // every wave is done reading the last stage
+#pragma unroll
+    for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          smem[acc_row(wm, tm, v, lane) * TILE + acc_col(wn, tn, lane)] = a.alpha * acc.t[tm][tn][v];
+    __syncthreads();
+    float* cbase = a.C + m0 * a.ldc + n0;
+    float4 cv[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int f = tid + u * WG_THREADS;
+      cv[u] = *reinterpret_cast<const float4*>(cbase + (int64_t)(f >> 5) * a.ldc + 4 * (f & 31));
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int f = tid + u * WG_THREADS;
+      const float4 d = *reinterpret_cast<const float4*>(smem + (f >> 5) * TILE + 4 * (f & 31));
+      cv[u].x += d.x; cv[u].y += d.y; cv[u].z += d.z; cv[u].w += d.w;
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int f = tid + u * WG_THREADS;
+      *reinterpret_cast<float4*>(cbase + (int64_t)(f >> 5) * a.ldc + 4 * (f & 31)) = cv[u];
+    }
   } else {
 #pragma unroll
     for (int tm = 0; tm < 2; ++tm)
