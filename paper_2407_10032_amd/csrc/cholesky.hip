@@ -575,6 +575,23 @@ __global__ __launch_bounds__(WG_THREADS) void chol_small_kernel(ChArgs a) {
         acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[x], bv[y], acc[x][y], 0, 0, 0);
   }
 
+  // old values first, all loads in flight together, then the stores
+  if (SUBTRACT) {
+#pragma unroll
+    for (int x = 0; x < NA; ++x)
+#pragma unroll
+      for (int y = 0; y < NBN; ++y) {
+        float old[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = wm * (TM / 2) + x * 32 + 8 * (v >> 2) + 4 * kl + (v & 3);
+          const int col = wn * (TN / 2) + y * 32 + ml;
+          old[v] = Out[(int64_t)row * ldo + col];
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[x][y][v] = old[v] - acc[x][y][v];
+      }
+  }
 #pragma unroll
   for (int x = 0; x < NA; ++x)
 #pragma unroll
@@ -583,9 +600,7 @@ __global__ __launch_bounds__(WG_THREADS) void chol_small_kernel(ChArgs a) {
       for (int v = 0; v < 16; ++v) {
         const int row = wm * (TM / 2) + x * 32 + 8 * (v >> 2) + 4 * kl + (v & 3);
         const int col = wn * (TN / 2) + y * 32 + ml;
-        float* o = Out + (int64_t)row * ldo + col;
-        if (SUBTRACT) *o -= acc[x][y][v];
-        else *o = acc[x][y][v];
+        Out[(int64_t)row * ldo + col] = acc[x][y][v];
       }
 }
 

@@ -461,20 +461,33 @@ __global__ __launch_bounds__(WG_THREADS) void tn_small_kernel(TnGemmArgs a) {
   const int K = (int)a.K;                    // <= 128, even
 
   const bool inner = VEC && (m0 + ST <= a.M) && (n0 + ST <= a.N);
-  for (int f = tid; f < 128 * (ST / 4); f += WG_THREADS) {
-    const int k = f / (ST / 4), c4 = f % (ST / 4);
-    float4 p = make_float4(0.f, 0.f, 0.f, 0.f), q = p;
-    if (k < K) {
-      if (inner) {
-        p = *reinterpret_cast<const float4*>(a.P + (int64_t)k * a.ldp + m0 + 4 * c4);
-        q = *reinterpret_cast<const float4*>(a.Q + (int64_t)k * a.ldq + n0 + 4 * c4);
-      } else {
-        p = tn_load_guarded<VEC>(a.P, a.ldp, k, K, m0 + 4 * c4, a.M);
-        q = tn_load_guarded<VEC>(a.Q, a.ldq, k, K, n0 + 4 * c4, a.N);
+  {
+    // 128 rows x 16 float4 per operand = 8 per thread and operand, all in flight together
+    constexpr int PER = 128 * (ST / 4) / WG_THREADS;
+    float4 p[PER], q[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int f = tid + u * WG_THREADS;
+      const int k = f / (ST / 4), c4 = f % (ST / 4);
+      p[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      q[u] = p[u];
+      if (k < K) {
+        if (inner) {
+          p[u] = *reinterpret_cast<const float4*>(a.P + (int64_t)k * a.ldp + m0 + 4 * c4);
+          q[u] = *reinterpret_cast<const float4*>(a.Q + (int64_t)k * a.ldq + n0 + 4 * c4);
+        } else {
+          p[u] = tn_load_guarded<VEC>(a.P, a.ldp, k, K, m0 + 4 * c4, a.M);
+          q[u] = tn_load_guarded<VEC>(a.Q, a.ldq, k, K, n0 + 4 * c4, a.N);
+        }
       }
     }
-    *reinterpret_cast<float4*>(sP + k * ST + 4 * c4) = p;
-    *reinterpret_cast<float4*>(sQ + k * ST + 4 * c4) = q;
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int f = tid + u * WG_THREADS;
+      const int k = f / (ST / 4), c4 = f % (ST / 4);
+      *reinterpret_cast<float4*>(sP + k * ST + 4 * c4) = p[u];
+      *reinterpret_cast<float4*>(sQ + k * ST + 4 * c4) = q[u];
+    }
   }
   __syncthreads();
 
@@ -487,11 +500,19 @@ __global__ __launch_bounds__(WG_THREADS) void tn_small_kernel(TnGemmArgs a) {
   for (int k = 0; k < 128; k += 2)
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pp[k * ST], pq[k * ST], acc, 0, 0, 0);
 
+  // all sixteen old values are loaded before the first store (a load after a store to a
+  // possibly aliasing address would wait for it)
+  const int64_t col = n0 + wn * 32 + ml;
+  float oldv[16];
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int64_t row = m0 + wm * 32 + 8 * (v >> 2) + 4 * kl + (v & 3);
-    const int64_t col = n0 + wn * 32 + ml;
-    if (row < a.M && col < a.N) a.C[row * a.ldc + col] += a.alpha * acc[v];
+    oldv[v] = (row < a.M && col < a.N) ? a.C[row * a.ldc + col] : 0.0f;
+  }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int64_t row = m0 + wm * 32 + 8 * (v >> 2) + 4 * kl + (v & 3);
+    if (row < a.M && col < a.N) a.C[row * a.ldc + col] = fmaf(a.alpha, acc[v], oldv[v]);
   }
 }
 
