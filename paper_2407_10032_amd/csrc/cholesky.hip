@@ -613,28 +613,31 @@ constexpr size_t chol_small_lds() {
 }
 
 // d[c-1-q] = sum_{p=q}^{c-1} Xb[p][q]^2 : column norms of L^-1 = diag(H_d^-1) reversed.
-// 32 columns per workgroup, 8 row-strided partial sums per column added in a fixed order.
-__global__ __launch_bounds__(256) void colnorm_kernel(const float* __restrict__ Xb, int64_t cp,
-                                                      int64_t c, float* __restrict__ d) {
-  __shared__ float part[8][33];
-  const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
-  const int64_t q = (int64_t)blockIdx.x * 32 + cx;
+// Two kernels: sums over slices of 128 rows (thread = column, so a row of the slice is one
+// coalesced read; slices entirely above the diagonal are skipped), then the slices of a
+// column are added in order.  part: [cp / 128][cp].
+__global__ __launch_bounds__(256) void colnorm_part_kernel(const float* __restrict__ Xb, int64_t cp,
+                                                           float* __restrict__ part) {
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t p0 = (int64_t)blockIdx.y * NB;
+  if (q >= cp) return;
+  if (p0 + NB <= (int64_t)blockIdx.x * 256) return;     // every row of the slice is above every column
   float s = 0.0f;
-  if (q < c) {
-    const int64_t p0 = (int64_t)blockIdx.x * 32;   // rows above the block's first column are zero
-    for (int64_t p = p0 + ry; p < c; p += 8) {
-      float x = (p >= q) ? Xb[p * cp + q] : 0.0f;
-      s = fmaf(x, x, s);
-    }
+#pragma unroll 8
+  for (int64_t p = p0; p < p0 + NB; ++p) {
+    const float x = (p >= q) ? Xb[p * cp + q] : 0.0f;
+    s = fmaf(x, x, s);
   }
-  part[ry][cx] = s;
-  __syncthreads();
-  if (ry == 0 && q < c) {
-    float t = 0.0f;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) t += part[k][cx];
-    d[c - 1 - q] = t;
-  }
+  part[(int64_t)blockIdx.y * cp + q] = s;
+}
+
+__global__ __launch_bounds__(256) void colnorm_sum_kernel(const float* __restrict__ part, int64_t cp,
+                                                          int64_t c, float* __restrict__ d) {
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= c) return;
+  float t = 0.0f;
+  for (int64_t sl = q / NB; sl < cp / NB; ++sl) t += part[sl * cp + q];
+  d[c - 1 - q] = t;
 }
 
 // U[a][b] = Xb[c-1-a][c-1-b] for b >= a, else 0.
@@ -793,9 +796,13 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
     }
   }
 
-  hipLaunchKernelGGL(colnorm_kernel, dim3((unsigned)lq::ceil_div(c, 32)), dim3(256), 0, st,
-                     (const float*)Xb, cp, c, hinv_diag);
-  LQ_CHECK_LAUNCH("colnorm_kernel");
+  // the factor workspace A is free once the inverse is complete: it holds the partial sums
+  hipLaunchKernelGGL(colnorm_part_kernel, dim3((unsigned)lq::ceil_div(cp, 256), (unsigned)nb), dim3(256), 0, st,
+                     (const float*)Xb, cp, A);
+  LQ_CHECK_LAUNCH("colnorm_part_kernel");
+  hipLaunchKernelGGL(colnorm_sum_kernel, dim3((unsigned)lq::ceil_div(c, 256)), dim3(256), 0, st,
+                     (const float*)A, cp, c, hinv_diag);
+  LQ_CHECK_LAUNCH("colnorm_sum_kernel");
   dim3 g3((unsigned)lq::ceil_div(c, 256), (unsigned)c);
   hipLaunchKernelGGL(flip_out_kernel, g3, dim3(256), 0, st, (const float*)Xb, cp, c, U, ldu);
   LQ_CHECK_LAUNCH("flip_out_kernel");
