@@ -155,6 +155,19 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     assert int(info.item()) == 0, "damped Hessian reported as not positive definite"
 
+    # the stored form of the result (packed codes + 16-bit tables): timed apart, it is not a
+    # step of Algorithm 1 and not part of `value`
+    packed = torch.empty((r, lq.lq_packed_row_bytes(c, P.bits)), dtype=torch.uint8, device="cuda")
+    table = torch.empty(grid.numel(), dtype=torch.int16, device="cuda")
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    lq.lq_pack_layer(codes, grid, P, packed, table)
+    pe[0].record()
+    for _ in range(5):
+        lq.lq_pack_layer(codes, grid, P, packed, table)
+    pe[1].record()
+    torch.cuda.synchronize()
+    pack_ms = pe[0].elapsed_time(pe[1]) / 5
+
     stage = np.array([[ev[k][i].elapsed_time(ev[k][i + 1]) for i in range(4)] for k in range(args.steps)])
     stage_ms = stage.mean(axis=0)
     # fp32 MFMA Gram product: tiles on or above the diagonal only, 2 flop per multiply-add
@@ -173,7 +186,8 @@ def main():
                    "stage_ms": {"hessian": stage_ms[0], "cholesky_inv": stage_ms[1], "fit_grid": stage_ms[2],
                                 "quantize_layer": stage_ms[3]},
                    # the same pass when H is reused from a projection with the same input
-                   "weights_per_s_without_hessian": r * c / (float(stage_ms[1:].sum()) * 1e-3)},
+                   "weights_per_s_without_hessian": r * c / (float(stage_ms[1:].sum()) * 1e-3),
+                   "pack_layer_ms": pack_ms, "bits_per_weight": lq.lq_bits_per_weight(r, c, P)},
         "roofline": {"bound": "mfma", "kernel": "tn_gemm_kernel (H += 2 X^T X, upper tiles) + partial-sum reduce",
                      "achieved": achieved, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / FP32_MFMA_PEAK_TFLOPS,

@@ -144,6 +144,32 @@ lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t ldw, const f
                             const float* grid, const lq_params* P, uint8_t* codes, float* row_loss,
                             void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Stored form of a quantized layer.  The "Bits" columns of the paper's result tables count b
+ * bits per weight plus sixteen bits per grid point per row (non-uniform grids: one set of 2^b
+ * points per row, Section 2.1) or per scale and per zero-point of a group (affine grids):
+ * 4.05 / 3.02 / 2.01 and 4.25 at group size 128.  The byte layout is this library's:
+ *   packed  [r x packed_ld] bytes, packed_ld >= lq_packed_row_bytes(c, bits): a row's codes
+ *           as a little-endian bit stream, code j in bits [j b, (j + 1) b) (bit k of the
+ *           stream is bit k % 8 of byte k / 8); unused high bits of the row's last byte are 0;
+ *   table   non-uniform: [r x 2^bits] IEEE binary16 bit patterns, the grid rounded to nearest
+ *           even; affine: [r x (c / group) x 2] = (binary16 S, int16 Z saturated to 16 bits).
+ * lq_pack_layer reads codes [r x c] (leading dimension c) and grid as written by
+ * lq_quantize_layer / lq_fit_grid for the same P.  lq_unpack_layer writes the weights the
+ * stored form stands for, W_hat[k][j] = table[k][code] or (code - Z) S of the column's group
+ * (Section 2.1), into W_hat [r x c] (ldw); they equal lq_quantize_layer's W up to the
+ * 16-bit rounding of the table.  codes (may be NULL) receives the unpacked codes [r x c].
+ * No workspace.  r = 0 is a no-op.
+ */
+int64_t lq_packed_row_bytes(int64_t c, int32_t bits);              /* ceil(c bits / 8); -1 if invalid */
+double lq_bits_per_weight(int64_t r, int64_t c, const lq_params* P); /* host only; -1 if invalid   */
+lq_status lq_pack_layer(const uint8_t* codes, const float* grid, int64_t r, int64_t c,
+                        const lq_params* P, uint8_t* packed, int64_t packed_ld, uint16_t* table,
+                        void* stream);
+lq_status lq_unpack_layer(const uint8_t* packed, int64_t packed_ld, const uint16_t* table, int64_t r,
+                          int64_t c, const lq_params* P, float* W_hat, int64_t ldw, uint8_t* codes,
+                          void* stream);
+
 /* Scratch bytes a call needs (host-only computation).  n_tokens is used by
  * LQ_CALL_HESSIAN only; r by FIT_GRID/QUANTIZE; P may be NULL for HESSIAN/CHOLESKY. */
 size_t lq_workspace_bytes(int which_call, int64_t r, int64_t c, int64_t n_tokens, const lq_params* P);

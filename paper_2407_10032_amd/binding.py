@@ -22,7 +22,8 @@ LQ_GRID_NONUNIFORM, LQ_GRID_AFFINE = 0, 1
 LQ_CALL_HESSIAN, LQ_CALL_CHOLESKY, LQ_CALL_FIT_GRID, LQ_CALL_QUANTIZE = range(4)
 
 EXPORTS = ("lq_params_default", "lq_hessian_accumulate", "lq_cholesky_inv", "lq_fit_grid",
-           "lq_quantize_layer", "lq_workspace_bytes", "lq_last_error", "lq_version")
+           "lq_quantize_layer", "lq_packed_row_bytes", "lq_bits_per_weight", "lq_pack_layer",
+           "lq_unpack_layer", "lq_workspace_bytes", "lq_last_error", "lq_version")
 
 
 class lq_params(ctypes.Structure):
@@ -62,6 +63,14 @@ def load() -> ctypes.CDLL:
     lib.lq_fit_grid.restype = ctypes.c_int
     lib.lq_quantize_layer.argtypes = [vp, i64, i64, i64, vp, i64, vp, pp, vp, vp, vp, sz, vp]
     lib.lq_quantize_layer.restype = ctypes.c_int
+    lib.lq_packed_row_bytes.argtypes = [i64, ctypes.c_int32]
+    lib.lq_packed_row_bytes.restype = i64
+    lib.lq_bits_per_weight.argtypes = [i64, i64, pp]
+    lib.lq_bits_per_weight.restype = ctypes.c_double
+    lib.lq_pack_layer.argtypes = [vp, vp, i64, i64, pp, vp, i64, vp, vp]
+    lib.lq_pack_layer.restype = ctypes.c_int
+    lib.lq_unpack_layer.argtypes = [vp, i64, vp, i64, i64, pp, vp, i64, vp, vp]
+    lib.lq_unpack_layer.restype = ctypes.c_int
     lib.lq_workspace_bytes.argtypes = [ctypes.c_int, i64, i64, i64, pp]
     lib.lq_workspace_bytes.restype = sz
     lib.lq_last_error.argtypes = []
@@ -162,6 +171,36 @@ def lq_quantize_layer(W: torch.Tensor, U: torch.Tensor, grid: torch.Tensor, P: l
                                     _ptr(grid, torch.float32, "grid"), ctypes.byref(P),
                                     _ptr(codes, torch.uint8, "codes"),
                                     _ptr(row_loss, torch.float32, "row_loss"), wp, wn, _stream()))
+
+
+def lq_packed_row_bytes(c: int, bits: int) -> int:
+    return int(load().lq_packed_row_bytes(c, bits))
+
+
+def lq_bits_per_weight(r: int, c: int, P: lq_params) -> float:
+    return float(load().lq_bits_per_weight(r, c, ctypes.byref(P)))
+
+
+def lq_pack_layer(codes: torch.Tensor, grid: torch.Tensor, P: lq_params, packed: torch.Tensor,
+                  table: torch.Tensor) -> None:
+    """codes [r x c] uint8 + grid -> packed [r x >= row_bytes] uint8, table int16 (bit patterns)."""
+    r, c = codes.shape
+    if not codes.is_contiguous():
+        raise ValueError("codes must be contiguous (leading dimension c)")
+    _check(load().lq_pack_layer(_ptr(codes, torch.uint8, "codes"), _ptr(grid, torch.float32, "grid"),
+                                r, c, ctypes.byref(P), _ptr(packed, torch.uint8, "packed"),
+                                _ld(packed, "packed"), _ptr(table, torch.int16, "table"), _stream()))
+
+
+def lq_unpack_layer(packed: torch.Tensor, table: torch.Tensor, c: int, P: lq_params,
+                    W_hat: torch.Tensor, codes: Optional[torch.Tensor]) -> None:
+    r = W_hat.shape[0]
+    if codes is not None and not codes.is_contiguous():
+        raise ValueError("codes must be contiguous (leading dimension c)")
+    _check(load().lq_unpack_layer(_ptr(packed, torch.uint8, "packed"), _ld(packed, "packed"),
+                                  _ptr(table, torch.int16, "table"), r, c, ctypes.byref(P),
+                                  _ptr(W_hat, torch.float32, "W_hat"), _ld(W_hat, "W_hat"),
+                                  _ptr(codes, torch.uint8, "codes"), _stream()))
 
 
 def lq_last_error() -> str:

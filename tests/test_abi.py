@@ -81,3 +81,22 @@ def test_binding_rejects_cpu_tensors():
     H = torch.zeros(4, 4)
     with pytest.raises(TypeError):
         lq.lq_hessian_accumulate(H, torch.zeros(2, 4), None)
+
+
+def test_host_side_packing_helpers_match_the_oracle():
+    """lq_packed_row_bytes and lq_bits_per_weight are host-only computations."""
+    from oracle import packing_oracle as po
+    import paper_2407_10032_amd as lq
+    lq.load()
+    for bits in (2, 3, 4):
+        for c in (1, 7, 8, 4096, 11008, 16384):
+            assert lq.lq_packed_row_bytes(c, bits) == po.packed_row_bytes(c, bits)
+            P = lq.lq_params_default(bits=bits, mode=lq.LQ_GRID_NONUNIFORM)
+            assert lq.lq_bits_per_weight(3, c, P) == po.bits_per_weight(3, c, bits, "nu")
+    P = lq.lq_params_default(bits=4, mode=lq.LQ_GRID_AFFINE, group_size=128)
+    assert lq.lq_bits_per_weight(3, 4096, P) == 4.25
+    P = lq.lq_params_default(bits=2, mode=lq.LQ_GRID_AFFINE, group_size=64)
+    assert lq.lq_bits_per_weight(3, 4096, P) == po.bits_per_weight(3, 4096, 2, "aff", 64) == 2.5
+    assert lq.lq_packed_row_bytes(-1, 4) == -1 and lq.lq_packed_row_bytes(8, 0) == -1
+    bad = lq.lq_params_default(bits=5)
+    assert lq.lq_bits_per_weight(3, 4096, bad) == -1.0
