@@ -16,6 +16,8 @@
 // partition the t_min range is walked and a grid scored whenever Z changes.
 #include <math.h>
 
+#include <type_traits>
+
 #include "lq_common.h"
 
 namespace {
@@ -162,17 +164,21 @@ __device__ __forceinline__ bool aff_better(double l, int k, const AffBest& b) {
   return (l < b.loss) || (l == b.loss && k < b.key);
 }
 
-__global__ __launch_bounds__(NT) void affine_search_kernel(const float* __restrict__ W, int64_t c,
-                                                           int64_t ldw, int g, int ngroups,
-                                                           const double* __restrict__ om64, int bits,
-                                                           int T, int t, float* __restrict__ SZ) {
+// NTA threads per group: the 2t + 1 values of s are dealt out NTA at a time, so the host
+// picks the NTA (64, 128 or 256) that leaves the fewest idle lanes in the last round.
+template <int NTA>
+__global__ __launch_bounds__(NTA) void affine_search_kernel(const float* __restrict__ W, int64_t c,
+                                                            int64_t ldw, int g, int ngroups,
+                                                            const double* __restrict__ om64, int bits,
+                                                            int T, int t, float* __restrict__ SZ) {
+  constexpr int NW = NTA / 64;
   extern __shared__ __align__(16) unsigned char smraw[];
   double* sOm = reinterpret_cast<double*>(smraw);          // [g]
   double* sW = sOm + g;                                    // [g]
-  __shared__ float sRed[8];
-  __shared__ double sBestLoss[NT];
-  __shared__ int sBestKey[NT];
-  __shared__ double sBestS[NT], sBestZ[NT];
+  __shared__ float sRed[2 * NW];
+  __shared__ double sBestLoss[NTA];
+  __shared__ int sBestKey[NTA];
+  __shared__ double sBestS[NTA], sBestZ[NTA];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t row = blockIdx.x / ngroups;
@@ -180,7 +186,7 @@ __global__ __launch_bounds__(NT) void affine_search_kernel(const float* __restri
   const float* wsrc = W + row * ldw + (int64_t)gi * g;
 
   float lo = INFINITY, hi = -INFINITY;
-  for (int i = tid; i < g; i += NT) {
+  for (int i = tid; i < g; i += NTA) {
     float x = wsrc[i];
     sW[i] = (double)x;
     sOm[i] = om64[(int64_t)gi * g + i];
@@ -189,10 +195,13 @@ __global__ __launch_bounds__(NT) void affine_search_kernel(const float* __restri
   }
   lo = wave_min(lo);
   hi = wave_max(hi);
-  if (lane == 0) { sRed[wave] = lo; sRed[4 + wave] = hi; }
+  if (lane == 0) { sRed[wave] = lo; sRed[NW + wave] = hi; }
   __syncthreads();
-  const double lo0 = (double)fminf(fminf(sRed[0], sRed[1]), fminf(sRed[2], sRed[3]));
-  const double hi0 = (double)fmaxf(fmaxf(sRed[4], sRed[5]), fmaxf(sRed[6], sRed[7]));
+  float lof = sRed[0], hif = sRed[NW];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) { lof = fminf(lof, sRed[w]); hif = fmaxf(hif, sRed[NW + w]); }
+  const double lo0 = (double)lof;
+  const double hi0 = (double)hif;
   const double R = hi0 - lo0;
   float* out = SZ + (row * ngroups + gi) * 2;
   if (R == 0.0) {  // constant group
@@ -217,35 +226,104 @@ __global__ __launch_bounds__(NT) void affine_search_kernel(const float* __restri
     }
     if (aff_better(loss, key, best)) { best.loss = loss; best.key = key; best.S = S; best.Z = Z; }
   };
+  // The same objective for ZC consecutive zero-points Z0, Z0 - 1, .. of one scale in a single
+  // pass over the weights: round(w / S) does not depend on Z, only the clipping does.  With
+  // CLIP32 the clipping is one fp32 median-of-three instead of an fp64 max and min (both
+  // half rate); round(w / S) and the bounds are integers below 2^23 in that case (checked per
+  // group), so the clipped value is the same number and every loss is bit-identical to score().
+  auto score_many = [&](auto zc_tag, auto clip_tag, double S, double Z0, double* loss) {
+    constexpr int ZC = decltype(zc_tag)::value;
+    constexpr bool CLIP32 = decltype(clip_tag)::value;
+    const double invS = 1.0 / S;
+    double l[ZC];
+    float clf[ZC], chf[ZC];
+#pragma unroll
+    for (int k = 0; k < ZC; ++k) {
+      l[k] = 0.0;
+      clf[k] = (float)(-(Z0 - (double)k));
+      chf[k] = (float)(qmax - (Z0 - (double)k));
+    }
+    for (int i = 0; i < g; ++i) {
+      const double w = sW[i], om = sOm[i];
+      const double u0 = rint(w * invS);
+      const float u0f = (float)u0;
+#pragma unroll
+      for (int k = 0; k < ZC; ++k) {
+        double u;
+        if (CLIP32) {
+          u = (double)__builtin_amdgcn_fmed3f(u0f, clf[k], chf[k]);
+        } else {
+          const double Z = Z0 - (double)k;
+          u = fmin(fmax(u0, -Z), qmax - Z);
+        }
+        const double dlt = fma(u, S, -w);
+        l[k] = fma(om * dlt, dlt, l[k]);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < ZC; ++k) loss[k] = l[k];
+  };
+  // |round(w / S)| and |Z| stay below 2^23 for every candidate of this group if
+  // max|w| / S_min does, with S_min = R (T - 2t) / (T (2^b - 1)) the smallest scale searched
+  const double smin = R * (double)(T - 2 * t) / (dT * qmax);
+  const bool clip32 = smin > 0.0 && fmax(fabs(lo0), fabs(hi0)) / smin < 4.0e6;
   // lo / S moves by (2^b - 1) / (T - s) per step of t_min.  When that is below one for every
   // s (T - 2t > 2^b - 1, true for the paper's T = 2048) the zero-points reached for a given s
   // are exactly the integers between the values at the two ends of the t_min range.
   const bool dense = (double)(T - 2 * t) > qmax;
-  for (int s = tid; s <= 2 * t; s += NT) {
+  const int rounds = (2 * t + NTA) / NTA;                 // every lane runs every round: the
+  for (int rd = 0; rd < rounds; ++rd) {                   // pass width is chosen per wavefront
+    const int s = tid + rd * NTA;
+    const bool live = s <= 2 * t;
     const int ta = (s > t) ? (s - t) : 0;      // smallest t_min with t_max = s - t_min <= t
     const int tb = (s < t) ? s : t;            // largest t_min
     if (dense) {
       const double lo_a = lo0 + (double)ta * R / dT;
       const double hi_a = hi0 - (double)(s - ta) * R / dT;
       const double S = (hi_a - lo_a) / qmax;
-      if (!(S > 0.0)) continue;
+      const bool ok = live && (S > 0.0);
+      const double Sx = ok ? S : 1.0;
       const double lo_b = lo0 + (double)tb * R / dT;
-      const double zf = -rint(lo_a / S);
-      const double zl = -rint(lo_b / S);
+      const double zf = -rint(lo_a / Sx);
+      const double zl = -rint(lo_b / Sx);
       double span = zf - zl;
       if (!(span >= 0.0)) span = 0.0;
-      const int nz = (int)fmin(span, 63.0) + 1;
-      for (int zi = 0; zi < nz; ++zi) {
-        const double Z = zf - (double)zi;
-        // first t_min of this class: smallest t_min >= ta with round(lo / S) == -Z
-        int tf = ta;
-        if (zi > 0) {
-          tf = (int)ceil(((-Z - 0.5) * S - lo0) * dT / R);
-          tf = tf < ta ? ta : (tf > tb ? tb : tf);
+      const int nz = ok ? (int)fmin(span, 63.0) + 1 : 0;
+      // widest class count in this wavefront decides how many zero-points share a pass
+      int nzw = nz;
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) nzw = max(nzw, __shfl_xor(nzw, o, 64));
+      for (int z0 = 0; z0 < nzw; ) {
+        double loss[4];
+        int cnt;
+        const double Z0 = zf - (double)z0;
+        cnt = nzw - z0 >= 4 ? 4 : nzw - z0;
+        if (clip32) {
+          if (cnt == 4) score_many(std::integral_constant<int, 4>{}, std::true_type{}, Sx, Z0, loss);
+          else if (cnt == 3) score_many(std::integral_constant<int, 3>{}, std::true_type{}, Sx, Z0, loss);
+          else if (cnt == 2) score_many(std::integral_constant<int, 2>{}, std::true_type{}, Sx, Z0, loss);
+          else score_many(std::integral_constant<int, 1>{}, std::true_type{}, Sx, Z0, loss);
+        } else {
+          if (cnt >= 2) { score_many(std::integral_constant<int, 2>{}, std::false_type{}, Sx, Z0, loss); cnt = 2; }
+          else score_many(std::integral_constant<int, 1>{}, std::false_type{}, Sx, Z0, loss);
         }
-        score(S, Z, tf * (t + 1) + (s - tf));
+        for (int k = 0; k < cnt; ++k) {
+          const int zi = z0 + k;
+          if (zi < nz) {
+            const double Z = zf - (double)zi;
+            // first t_min of this class: smallest t_min >= ta with round(lo / S) == -Z
+            int tf = ta;
+            if (zi > 0) {
+              tf = (int)ceil(((-Z - 0.5) * S - lo0) * dT / R);
+              tf = tf < ta ? ta : (tf > tb ? tb : tf);
+            }
+            const int key = tf * (t + 1) + (s - tf);
+            if (aff_better(loss[k], key, best)) { best.loss = loss[k]; best.key = key; best.S = S; best.Z = Z; }
+          }
+        }
+        z0 += cnt;
       }
-    } else {
+    } else if (live) {
       double zprev = 0.0;
       for (int tm = ta; tm <= tb; ++tm) {
         const double lo_c = lo0 + (double)tm * R / dT;
@@ -260,7 +338,7 @@ __global__ __launch_bounds__(NT) void affine_search_kernel(const float* __restri
   }
   sBestLoss[tid] = best.loss; sBestKey[tid] = best.key; sBestS[tid] = best.S; sBestZ[tid] = best.Z;
   __syncthreads();
-  for (int w2 = NT / 2; w2 > 0; w2 >>= 1) {
+  for (int w2 = NTA / 2; w2 > 0; w2 >>= 1) {
     if (tid < w2) {
       AffBest o;
       o.loss = sBestLoss[tid]; o.key = sBestKey[tid];
@@ -337,14 +415,34 @@ extern "C" lq_status lq_fit_grid(const float* W, int64_t r, int64_t c, int64_t l
   hipLaunchKernelGGL(importance_kernel, dim3(1), dim3(1024), 0, st, hinv_diag, c, P->p, om32, om64);
   LQ_CHECK_LAUNCH("importance_kernel");
   const size_t lds = (size_t)g * 2 * sizeof(double);
-  static size_t lds_set = 0;
-  if (lds > lds_set) {
-    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)affine_search_kernel,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)(8192 * 16)));
-    lds_set = 8192 * 16;
+  const int t = lq::resolve_t(P);
+  const int ns = 2 * t + 1;
+  // threads per group: fewest idle lanes in the last round of s values; ties go to the larger
+  int nta = 256;
+  {
+    int best = (ns + 255) / 256 * 256;
+    for (int cand : {128, 64}) {
+      const int padded = (ns + cand - 1) / cand * cand;
+      if (padded < best) { best = padded; nta = cand; }
+    }
   }
-  hipLaunchKernelGGL(affine_search_kernel, dim3((unsigned)(r * ngroups)), dim3(NT), lds, st, W, c, ldw,
-                     (int)g, (int)ngroups, (const double*)om64, P->bits, P->T, lq::resolve_t(P), grid);
+  static bool attr_done = false;
+  if (!attr_done) {
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)affine_search_kernel<64>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)(8192 * 16)));
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)affine_search_kernel<128>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)(8192 * 16)));
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)affine_search_kernel<256>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)(8192 * 16)));
+    attr_done = true;
+  }
+  const dim3 ggrid((unsigned)(r * ngroups));
+#define LQ_AFF(N) hipLaunchKernelGGL(affine_search_kernel<N>, ggrid, dim3(N), lds, st, W, c, ldw, (int)g, \
+                                     (int)ngroups, (const double*)om64, P->bits, P->T, t, grid)
+  if (nta == 64) LQ_AFF(64);
+  else if (nta == 128) LQ_AFF(128);
+  else LQ_AFF(256);
+#undef LQ_AFF
   LQ_CHECK_LAUNCH("affine_search_kernel");
   return LQ_OK;
 }

@@ -111,31 +111,19 @@ __device__ __forceinline__ float4 tn_load_guarded(const float* __restrict__ base
   return v;
 }
 
-// FAST: the whole chunk is inside the matrix and 16-byte aligned: no predicates, a
-// wave-uniform row base (scalar registers) plus a 32-bit per-thread offset.
-template <int KT, bool VEC, bool FAST>
+// One guarded k-chunk of an operand: rows past kend and columns past ncols read as zero.
+template <int KT, bool VEC>
 __device__ __forceinline__ ChunkRegs<KT> tn_load_chunk(const float* __restrict__ base, int64_t ld,
                                                        int64_t k0, int64_t kend, int64_t col0,
                                                        int64_t ncols, int tid) {
   ChunkRegs<KT> c;
-  if (FAST) {
-    const float* rowbase = base + k0 * ld + col0;
-    const int off = (tid >> 5) * (int)ld + 4 * (tid & 31);
-    c.r0 = *reinterpret_cast<const float4*>(rowbase + off);
-    c.r1 = *reinterpret_cast<const float4*>(rowbase + (off + 8 * (int)ld));
-    if constexpr (KT == 32) {
-      c.r2 = *reinterpret_cast<const float4*>(rowbase + (off + 16 * (int)ld));
-      c.r3 = *reinterpret_cast<const float4*>(rowbase + (off + 24 * (int)ld));
-    }
-  } else {
-    const int64_t k = k0 + (tid >> 5);
-    const int64_t col = col0 + 4 * (tid & 31);
-    c.r0 = tn_load_guarded<VEC>(base, ld, k, kend, col, ncols);
-    c.r1 = tn_load_guarded<VEC>(base, ld, k + 8, kend, col, ncols);
-    if constexpr (KT == 32) {
-      c.r2 = tn_load_guarded<VEC>(base, ld, k + 16, kend, col, ncols);
-      c.r3 = tn_load_guarded<VEC>(base, ld, k + 24, kend, col, ncols);
-    }
+  const int64_t k = k0 + (tid >> 5);
+  const int64_t col = col0 + 4 * (tid & 31);
+  c.r0 = tn_load_guarded<VEC>(base, ld, k, kend, col, ncols);
+  c.r1 = tn_load_guarded<VEC>(base, ld, k + 8, kend, col, ncols);
+  if constexpr (KT == 32) {
+    c.r2 = tn_load_guarded<VEC>(base, ld, k + 16, kend, col, ncols);
+    c.r3 = tn_load_guarded<VEC>(base, ld, k + 24, kend, col, ncols);
   }
   return c;
 }
@@ -159,9 +147,9 @@ __device__ __forceinline__ void tn_mainloop_safe(const TnGemmArgs& a, float* sme
                                                  int64_t kend, int64_t m0, int64_t n0, bool diag,
                                                  int wm, int wn, int lane, int tid, Acc2x2& acc) {
   constexpr int STAGE = KT * TILE;
-  ChunkRegs<KT> rp = tn_load_chunk<KT, VEC, false>(a.P, a.ldp, kbeg, kend, m0, a.M, tid);
+  ChunkRegs<KT> rp = tn_load_chunk<KT, VEC>(a.P, a.ldp, kbeg, kend, m0, a.M, tid);
   ChunkRegs<KT> rq = rp;
-  if (!diag) rq = tn_load_chunk<KT, VEC, false>(a.Q, a.ldq, kbeg, kend, n0, a.N, tid);
+  if (!diag) rq = tn_load_chunk<KT, VEC>(a.Q, a.ldq, kbeg, kend, n0, a.N, tid);
   tn_store_chunk<KT>(smem, rp, tid);
   if (!diag) tn_store_chunk<KT>(smem + 2 * STAGE, rq, tid);
   __syncthreads();
@@ -169,8 +157,8 @@ __device__ __forceinline__ void tn_mainloop_safe(const TnGemmArgs& a, float* sme
   for (int64_t k0 = kbeg; k0 < kend; k0 += KT) {
     const bool more = (k0 + KT) < kend;
     if (more) {
-      rp = tn_load_chunk<KT, VEC, false>(a.P, a.ldp, k0 + KT, kend, m0, a.M, tid);
-      if (!diag) rq = tn_load_chunk<KT, VEC, false>(a.Q, a.ldq, k0 + KT, kend, n0, a.N, tid);
+      rp = tn_load_chunk<KT, VEC>(a.P, a.ldp, k0 + KT, kend, m0, a.M, tid);
+      if (!diag) rq = tn_load_chunk<KT, VEC>(a.Q, a.ldq, k0 + KT, kend, n0, a.N, tid);
     }
     const float* cp = smem + buf * STAGE;
     mma_chunk_kmajor<KT>(cp, diag ? cp : cp + 2 * STAGE, wm, wn, lane, acc);
