@@ -14,8 +14,7 @@ namespace {
 constexpr int KT = 32;                       // tokens per LDS stage (64 KB of LDS, two workgroups per CU;
                                              // 16-token stages at four per CU measured 2 % slower)
 constexpr int MINW = 2;
-constexpr int64_t MIN_TOKENS_PER_SPLIT = 256;
-constexpr int64_t TARGET_WORKGROUPS = 16384; // ~32 resident rounds of 2 workgroups per CU: short tail
+constexpr int MAX_SPLITS = 64;
 
 struct HessianPlan {
   int T;        // tiles per dimension
@@ -25,19 +24,37 @@ struct HessianPlan {
   size_t ws_bytes;
 };
 
+// The token range is cut into `splits` slices.  More slices mean more, shorter workgroups:
+// a shorter tail at the end of the launch, but a larger share of each workgroup spent on its
+// first loads and its partial-tile store, and more partial tiles for the reduce kernel to
+// read.  The number of slices is the one that minimizes a small time model of these three
+// effects (constants measured on MI355X: 3.56 us per 32-token stage of a workgroup that
+// shares its compute unit with a second one, about 6 us of fixed cost per workgroup, half a
+// round of tail once the launch exceeds the resident slots, 3 TB/s for the reduce kernel).
 HessianPlan make_plan(int64_t c, int64_t n_tokens) {
   HessianPlan p;
   p.T = (int)lq::ceil_div(c, lq::TILE);
   p.ntiles = p.T * (p.T + 1) / 2;
-  int64_t want = lq::ceil_div(TARGET_WORKGROUPS, p.ntiles);
-  int64_t most = n_tokens / MIN_TOKENS_PER_SPLIT;
-  if (most < 1) most = 1;
-  int64_t s = want < most ? want : most;
-  if (s < 1) s = 1;
-  int64_t per = lq::ceil_div(n_tokens > 0 ? n_tokens : 1, s);
-  per = lq::ceil_div(per, KT) * KT;
+  const int64_t n = n_tokens > 0 ? n_tokens : 1;
+  const double slots = 512.0;                  // 256 compute units x 2 resident workgroups
+  const double stage_us = 3.56, fixed_us = 6.0;
+  int best_s = 1;
+  double best_t = 0.0;
+  for (int s = 1; s <= MAX_SPLITS; ++s) {
+    int64_t per = lq::ceil_div(lq::ceil_div(n, (int64_t)s), (int64_t)KT) * KT;
+    const int64_t used = lq::ceil_div(n, per);
+    if (used != s) continue;                   // the same slicing as a smaller s
+    const double stages = (double)per / KT;
+    const double wgs = (double)p.ntiles * (double)used;
+    const double rounds = wgs <= slots ? 1.0 : wgs / slots + 0.5;
+    const double t_main = rounds * (stages * stage_us + fixed_us);
+    const double t_reduce = wgs * (lq::TILE * lq::TILE * 4.0) / 3.0e6;   // bytes / (3 TB/s) in us
+    const double t = t_main + t_reduce;
+    if (s == 1 || t < best_t) { best_t = t; best_s = s; }
+  }
+  int64_t per = lq::ceil_div(lq::ceil_div(n, (int64_t)best_s), (int64_t)KT) * KT;
   p.k_per_split = per;
-  p.splits = (int)lq::ceil_div(n_tokens > 0 ? n_tokens : 1, per);
+  p.splits = (int)lq::ceil_div(n, per);
   p.ws_bytes = (size_t)p.splits * p.ntiles * lq::TILE * lq::TILE * sizeof(float);
   return p;
 }

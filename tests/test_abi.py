@@ -36,7 +36,7 @@ def test_defaults_are_the_papers_settings():
 def test_workspace_sizes():
     P = lq.lq_params_default()
     assert lq.lq_workspace_bytes(lq.LQ_CALL_HESSIAN, 0, 4096, 262144) == 32 * 528 * 128 * 128 * 4
-    assert lq.lq_workspace_bytes(lq.LQ_CALL_HESSIAN, 0, 16384, 65536) == 2 * 8256 * 128 * 128 * 4
+    assert lq.lq_workspace_bytes(lq.LQ_CALL_HESSIAN, 0, 16384, 65536) == 4 * 8256 * 128 * 128 * 4
     assert lq.lq_workspace_bytes(lq.LQ_CALL_CHOLESKY, 0, 200) >= 2 * 256 * 256 * 4 + 2 * 128 * 128 * 4
     assert lq.lq_workspace_bytes(lq.LQ_CALL_QUANTIZE, 100, 512, 0, P) >= (100 + 4 * 128 + 4) * 128 * 4
     assert lq.lq_workspace_bytes(lq.LQ_CALL_FIT_GRID, 10, 512, 0, P) >= 512 * 12
