@@ -126,6 +126,17 @@ lq_status lq_fit_grid(const float* W, int64_t r, int64_t c, int64_t ldw, const f
                       const lq_params* P, float* grid, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * lq_fit_grid with a caller-supplied starting grid for the weighted k-means of Eq. 5 instead of
+ * Eq. 6's evenly spaced one (the paper's appendix compares Eq. 6 against k-means++ seeding; any
+ * seeding can be computed by the caller and passed here).
+ *   init_grid  [r x 2^bits] ascending, or NULL for Eq. 6 (then identical to lq_fit_grid).
+ * Non-uniform mode only (an initial grid with an affine P is an argument error).
+ */
+lq_status lq_fit_grid_from(const float* W, int64_t r, int64_t c, int64_t ldw, const float* hinv_diag,
+                           const lq_params* P, const float* init_grid, float* grid, void* ws,
+                           size_t ws_bytes, void* stream);
+
+/*
  * Algorithm 1 lines 10-21: for each block of B columns, quantize column by column
  * against the row's grid, scale the error by U_jj, propagate it inside the block,
  * then apply the dense rank-B update to all later columns.

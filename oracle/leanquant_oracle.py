@@ -169,6 +169,40 @@ def fit_grid_nu(W, d, bits, p, max_iter=100, init=None, history=None):
     return G
 
 
+def kmeanspp_init(W, d, bits, p, u):
+    """Weighted k-means++ seeding, the initialisation the paper's appendix table on grid
+    point initialisation compares Eq. 6 against (Arthur & Vassilvitskii's D^2 sampling with
+    the importance weights of Eq. 5 as point masses).
+
+    u [r x 2^b] are uniform numbers in [0, 1) supplied by the caller (one per centre), so
+    that the procedure is a function of its inputs.  Centre 0 of a row is drawn with
+    probability proportional to omega_i, centre m with probability proportional to
+    omega_i * min_j (w_i - g_j)^2; a draw takes the first index whose cumulative mass
+    reaches u * total.  If every remaining mass is zero the first column is taken.  Returns
+    the centres of every row in ascending order.
+    """
+    W = np.atleast_2d(np.asarray(W, dtype=F64))
+    omega = importance(d, p)
+    r, c = W.shape
+    K = 1 << bits
+    u = np.asarray(u, dtype=F64).reshape(r, K)
+    G = np.empty((r, K), dtype=F64)
+    for k in range(r):
+        w = W[k]
+        dist2 = np.full(c, np.inf)
+        for m in range(K):
+            mass = omega if m == 0 else omega * dist2
+            cum = np.cumsum(mass)
+            total = cum[-1]
+            i = 0 if not (total > 0.0) else int(min(np.searchsorted(cum, u[k, m] * total, side="left"), c - 1))
+            if total > 0.0:
+                while mass[i] == 0.0 and i + 1 < c:      # u = 0 or flat steps: a point with mass
+                    i += 1
+            G[k, m] = w[i]
+            dist2 = np.minimum(dist2, (w - w[i]) ** 2)
+    return np.sort(G, axis=1)
+
+
 def shrink_steps(bits, T):
     """Eq. 8: t = 0.2T / 0.3T / 0.4T for b = 4 / 3 / 2, floored to an integer."""
     frac = {4: 0.2, 3: 0.3, 2: 0.4}[bits]

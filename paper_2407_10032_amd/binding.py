@@ -22,7 +22,7 @@ LQ_GRID_NONUNIFORM, LQ_GRID_AFFINE = 0, 1
 LQ_CALL_HESSIAN, LQ_CALL_CHOLESKY, LQ_CALL_FIT_GRID, LQ_CALL_QUANTIZE = range(4)
 
 EXPORTS = ("lq_params_default", "lq_hessian_accumulate", "lq_cholesky_inv", "lq_fit_grid",
-           "lq_quantize_layer", "lq_packed_row_bytes", "lq_bits_per_weight", "lq_pack_layer",
+           "lq_fit_grid_from", "lq_quantize_layer", "lq_packed_row_bytes", "lq_bits_per_weight", "lq_pack_layer",
            "lq_unpack_layer", "lq_workspace_bytes", "lq_last_error", "lq_version")
 
 
@@ -61,6 +61,8 @@ def load() -> ctypes.CDLL:
     lib.lq_cholesky_inv.restype = ctypes.c_int
     lib.lq_fit_grid.argtypes = [vp, i64, i64, i64, vp, pp, vp, vp, sz, vp]
     lib.lq_fit_grid.restype = ctypes.c_int
+    lib.lq_fit_grid_from.argtypes = [vp, i64, i64, i64, vp, pp, vp, vp, vp, sz, vp]
+    lib.lq_fit_grid_from.restype = ctypes.c_int
     lib.lq_quantize_layer.argtypes = [vp, i64, i64, i64, vp, i64, vp, pp, vp, vp, vp, sz, vp]
     lib.lq_quantize_layer.restype = ctypes.c_int
     lib.lq_packed_row_bytes.argtypes = [i64, ctypes.c_int32]
@@ -160,6 +162,18 @@ def lq_fit_grid(W: torch.Tensor, hinv_diag: torch.Tensor, P: lq_params, grid: to
     _check(load().lq_fit_grid(_ptr(W, torch.float32, "W"), r, c, _ld(W, "W"),
                               _ptr(hinv_diag, torch.float32, "hinv_diag"), ctypes.byref(P),
                               _ptr(grid, torch.float32, "grid"), wp, wn, _stream()))
+
+
+def lq_fit_grid_from(W: torch.Tensor, hinv_diag: torch.Tensor, P: lq_params,
+                     init_grid: Optional[torch.Tensor], grid: torch.Tensor, ws: torch.Tensor) -> None:
+    r, c = W.shape
+    wp, wn = _ws(ws)
+    if init_grid is not None and not init_grid.is_contiguous():
+        raise ValueError("init_grid must be contiguous")
+    _check(load().lq_fit_grid_from(_ptr(W, torch.float32, "W"), r, c, _ld(W, "W"),
+                                   _ptr(hinv_diag, torch.float32, "hinv_diag"), ctypes.byref(P),
+                                   _ptr(init_grid, torch.float32, "init_grid"),
+                                   _ptr(grid, torch.float32, "grid"), wp, wn, _stream()))
 
 
 def lq_quantize_layer(W: torch.Tensor, U: torch.Tensor, grid: torch.Tensor, P: lq_params,

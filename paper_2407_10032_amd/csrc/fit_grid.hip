@@ -63,6 +63,7 @@ template <int K, int EPT>
 __global__ __launch_bounds__(NT) void kmeans_rows_kernel(const float* __restrict__ W, int64_t r,
                                                          int64_t c, int64_t ldw,
                                                          const float* __restrict__ om32,
+                                                         const float* __restrict__ init,
                                                          int max_iter, float* __restrict__ G) {
   constexpr int ACC_LD = 2 * K + 1;
   constexpr int PARTS = NT / (2 * K);   // threads that share one column of the reduction
@@ -103,8 +104,8 @@ __global__ __launch_bounds__(NT) void kmeans_rows_kernel(const float* __restrict
     __syncthreads();
     lo = fminf(fminf(sRed[0], sRed[1]), fminf(sRed[2], sRed[3]));
     hi = fmaxf(fmaxf(sRed[4], sRed[5]), fmaxf(sRed[6], sRed[7]));
-    // Eq. 6: evenly spaced initial grid from min to max
-    if (tid < K) sG[tid] = lo + (hi - lo) / (float)(K - 1) * (float)tid;
+    // Eq. 6: evenly spaced initial grid from min to max, unless the caller supplies one
+    if (tid < K) sG[tid] = init ? init[row * K + tid] : lo + (hi - lo) / (float)(K - 1) * (float)tid;
     __syncthreads();
 
     for (int it = 0; it < max_iter; ++it) {
@@ -354,12 +355,12 @@ __global__ __launch_bounds__(NTA) void affine_search_kernel(const float* __restr
 
 template <int K>
 lq_status launch_kmeans(const float* W, int64_t r, int64_t c, int64_t ldw, const float* om32,
-                        int max_iter, float* G, hipStream_t st) {
+                        const float* init, int max_iter, float* G, hipStream_t st) {
   int64_t ept = lq::ceil_div(c, NT);
   unsigned grid = (unsigned)(r < 2048 ? r : 2048);
 #define LQ_KM(E)                                                                              \
   hipLaunchKernelGGL((kmeans_rows_kernel<K, E>), dim3(grid), dim3(NT), 0, st, W, r, c, ldw, \
-                     om32, max_iter, G)
+                     om32, init, max_iter, G)
   if (ept <= 2) LQ_KM(2);
   else if (ept <= 4) LQ_KM(4);
   else if (ept <= 8) LQ_KM(8);
@@ -380,9 +381,31 @@ size_t fit_grid_workspace_bytes(int64_t c) {
 }
 }  // namespace lq
 
+namespace {
+lq_status fit_grid_impl(const float* W, int64_t r, int64_t c, int64_t ldw, const float* hinv_diag,
+                        const lq_params* P, const float* init_grid, float* grid, void* ws,
+                        size_t ws_bytes, void* stream);
+}
+
 extern "C" lq_status lq_fit_grid(const float* W, int64_t r, int64_t c, int64_t ldw,
                                  const float* hinv_diag, const lq_params* P, float* grid, void* ws,
                                  size_t ws_bytes, void* stream) {
+  return fit_grid_impl(W, r, c, ldw, hinv_diag, P, nullptr, grid, ws, ws_bytes, stream);
+}
+
+extern "C" lq_status lq_fit_grid_from(const float* W, int64_t r, int64_t c, int64_t ldw,
+                                      const float* hinv_diag, const lq_params* P,
+                                      const float* init_grid, float* grid, void* ws, size_t ws_bytes,
+                                      void* stream) {
+  if (P && P->mode != LQ_GRID_NONUNIFORM && init_grid)
+    return lq::fail(LQ_ERR_INVALID_ARG, "lq_fit_grid_from: an initial grid applies to non-uniform grids only");
+  return fit_grid_impl(W, r, c, ldw, hinv_diag, P, init_grid, grid, ws, ws_bytes, stream);
+}
+
+namespace {
+lq_status fit_grid_impl(const float* W, int64_t r, int64_t c, int64_t ldw, const float* hinv_diag,
+                        const lq_params* P, const float* init_grid, float* grid, void* ws,
+                        size_t ws_bytes, void* stream) {
   if (r == 0 && c >= 1) return LQ_OK;   // nothing to do; empty buffers may be null
   if (!W || !hinv_diag || !grid) return lq::fail(LQ_ERR_INVALID_ARG, "lq_fit_grid: null pointer");
   if (r < 0 || c < 1 || ldw < c) return lq::fail(LQ_ERR_INVALID_ARG, "lq_fit_grid: r=%lld c=%lld ldw=%lld", (long long)r, (long long)c, (long long)ldw);
@@ -402,9 +425,9 @@ extern "C" lq_status lq_fit_grid(const float* W, int64_t r, int64_t c, int64_t l
     hipLaunchKernelGGL(importance_kernel, dim3(1), dim3(1024), 0, st, hinv_diag, c, P->p, om32, om64);
     LQ_CHECK_LAUNCH("importance_kernel");
     switch (P->bits) {
-      case 2: return launch_kmeans<4>(W, r, c, ldw, om32, P->kmeans_max_iter, grid, st);
-      case 3: return launch_kmeans<8>(W, r, c, ldw, om32, P->kmeans_max_iter, grid, st);
-      default: return launch_kmeans<16>(W, r, c, ldw, om32, P->kmeans_max_iter, grid, st);
+      case 2: return launch_kmeans<4>(W, r, c, ldw, om32, init_grid, P->kmeans_max_iter, grid, st);
+      case 3: return launch_kmeans<8>(W, r, c, ldw, om32, init_grid, P->kmeans_max_iter, grid, st);
+      default: return launch_kmeans<16>(W, r, c, ldw, om32, init_grid, P->kmeans_max_iter, grid, st);
     }
   }
 
@@ -446,3 +469,5 @@ extern "C" lq_status lq_fit_grid(const float* W, int64_t r, int64_t c, int64_t l
   LQ_CHECK_LAUNCH("affine_search_kernel");
   return LQ_OK;
 }
+}  // namespace
+

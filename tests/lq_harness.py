@@ -54,11 +54,14 @@ def grid_shape(P, r, c):
     return (r, c // g, 2)
 
 
-def gpu_fit_grid(W, d, P):
+def gpu_fit_grid(W, d, P, init=None):
     r, c = W.shape
     grid = torch.empty(grid_shape(P, r, c), dtype=torch.float32, device=DEV)
     ws = lq.alloc_workspace(lq.lq_workspace_bytes(lq.LQ_CALL_FIT_GRID, r, c, 0, P))
-    lq.lq_fit_grid(W, d, P, grid, ws)
+    if init is None:
+        lq.lq_fit_grid(W, d, P, grid, ws)
+    else:
+        lq.lq_fit_grid_from(W, d, P, init, grid, ws)
     torch.cuda.synchronize()
     return grid
 

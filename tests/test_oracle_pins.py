@@ -463,3 +463,44 @@ def test_invariances_of_whole_pass():
     ba = orc.leanquant_layer(W, H, "aff", 3, B=8, group_size=16, T=32)
     sa = orc.leanquant_layer(W, 0.01 * H, "aff", 3, B=8, group_size=16, T=32)
     np.testing.assert_array_equal(sa["codes"], ba["codes"])
+
+
+# ------------------------------------------------------------------ k-means++ seeding
+def test_kmeanspp_hand_computed_draws():
+    # w = [0, 1, 3], equal masses.  u0 = 0.5: cumulative masses [1, 2, 3], target 1.5 -> index 1
+    # (w = 1).  Then D^2 = [1, 0, 4], cumulative [1, 1, 5], u1 = 0.5 -> target 2.5 -> index 2.
+    G = orc.kmeanspp_init(np.array([[0.0, 1.0, 3.0]]), np.ones(3), 1, 1.0, np.array([[0.5, 0.5]]))
+    assert G.tolist() == [[1.0, 3.0]]
+    # u1 = 0.1 -> target 0.5 -> index 0 (w = 0)
+    G = orc.kmeanspp_init(np.array([[0.0, 1.0, 3.0]]), np.ones(3), 1, 1.0, np.array([[0.5, 0.1]]))
+    assert G.tolist() == [[0.0, 1.0]]
+
+
+def test_kmeanspp_centres_are_distinct_points_of_the_row_and_follow_the_masses():
+    rng = np.random.default_rng(11)
+    W = rng.standard_normal((40, 64))
+    d = np.exp(rng.standard_normal(64))
+    G = orc.kmeanspp_init(W, d, 3, 4.0, rng.random((40, 8)))
+    for k in range(40):
+        assert np.all(np.isin(G[k], W[k]))
+        assert len(np.unique(G[k])) == 8            # a chosen point has D^2 = 0 afterwards
+        assert np.all(np.diff(G[k]) > 0)
+    # first centre: frequency of column i over many draws is proportional to omega_i
+    om = orc.importance(np.array([1.0, 2.0 ** -0.25, 1.0]), 4.0)      # masses 1 : 2 : 1 -> scaled
+    w = np.array([[-1.0, 0.0, 1.0]])
+    picks = [orc.kmeanspp_init(w, np.array([1.0, 2.0 ** -0.25, 1.0]), 0, 4.0, np.array([[u]]))[0, 0]
+             for u in (np.arange(1000) + 0.5) / 1000]
+    share = np.mean(np.array(picks) == 0.0)
+    assert abs(share - om[1] / om.sum()) < 2e-3
+
+
+def test_lloyd_from_kmeanspp_init_does_not_increase_the_objective():
+    rng = np.random.default_rng(12)
+    W = rng.standard_normal((6, 200)) * 0.02
+    d = np.exp(rng.standard_normal(200))
+    init = orc.kmeanspp_init(W, d, 3, 4.0, rng.random((6, 8)))
+    hist = []
+    G = orc.fit_grid_nu(W, d, 3, 4.0, init=init, history=hist)
+    H = np.array(hist)
+    assert np.all(np.diff(H, axis=0) <= 1e-18 + 1e-12 * H[:-1])
+    assert np.all(np.diff(G, axis=1) >= 0)
