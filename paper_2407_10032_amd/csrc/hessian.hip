@@ -106,7 +106,7 @@ extern "C" lq_status lq_hessian_accumulate(float* H, int64_t ldh, const float* X
   else
     hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, true, true, false, MINW>), grid, block, lds, st, a);
   LQ_CHECK_LAUNCH("tn_gemm_kernel(hessian)");
-  hipLaunchKernelGGL(lq::tn_reduce_sym_kernel, dim3(plan.ntiles), block, 0, st, (const float*)ws,
+  hipLaunchKernelGGL(lq::tn_reduce_sym_kernel, dim3(4 * plan.ntiles), block, 0, st, (const float*)ws,
                      plan.splits, plan.ntiles, plan.T, H, ldh, c, 2.0f);
   LQ_CHECK_LAUNCH("tn_reduce_sym_kernel");
   return LQ_OK;

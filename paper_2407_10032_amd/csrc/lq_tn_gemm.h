@@ -505,18 +505,20 @@ __global__ __launch_bounds__(WG_THREADS) void tn_small_kernel(TnGemmArgs a) {
 }
 
 // Sum the token-split partial tiles in split order and add alpha * sum to C, writing
-// the tile at (bi, bj) and its transpose at (bj, bi).  One workgroup per upper tile.
+// the tile at (bi, bj) and its transpose at (bj, bi).  Four workgroups per upper tile.
 static __global__ __launch_bounds__(WG_THREADS) void tn_reduce_sym_kernel(const float* __restrict__ partial,
                                                                   int splits, int ntiles, int T,
                                                                   float* __restrict__ C, int64_t ldc,
                                                                   int64_t M, float alpha) {
   __shared__ float st[32 * 129];
   const int tid = threadIdx.x;
-  const int tile = blockIdx.x;
+  const int tile = blockIdx.x >> 2;        // four workgroups per tile, 32 rows each
   int bi, bj;
   decode_patch_major<true>(tile, T, T, bi, bj);
   const int64_t m0 = (int64_t)bi * TILE, n0 = (int64_t)bj * TILE;
-  for (int sb = 0; sb < 4; ++sb) {
+  const bool vecc = (ldc % 4 == 0) && ((reinterpret_cast<uintptr_t>(C) & 15) == 0);
+  {
+    const int sb = blockIdx.x & 3;
     // rows sb*32 .. sb*32+31 of the tile: 32 x 128 values, 16 per thread
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
@@ -524,6 +526,8 @@ static __global__ __launch_bounds__(WG_THREADS) void tn_reduce_sym_kernel(const 
       int lr = f >> 5, c4 = f & 31;
       const float* src = partial + (int64_t)tile * (TILE * TILE) + (sb * 32 + lr) * TILE + 4 * c4;
       float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+      // slices are added in order; eight loads are in flight at a time
+#pragma unroll 8
       for (int sp = 0; sp < splits; ++sp) {
         float4 v = *reinterpret_cast<const float4*>(src + (int64_t)sp * ntiles * (TILE * TILE));
         s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
@@ -533,22 +537,37 @@ static __global__ __launch_bounds__(WG_THREADS) void tn_reduce_sym_kernel(const 
       int64_t col = n0 + 4 * c4;
       if (row < M) {
         float* dst = C + row * ldc + col;
-        if (col + 0 < M) dst[0] += s.x;
-        if (col + 1 < M) dst[1] += s.y;
-        if (col + 2 < M) dst[2] += s.z;
-        if (col + 3 < M) dst[3] += s.w;
+        if (vecc && col + 3 < M) {
+          float4 o = *reinterpret_cast<const float4*>(dst);
+          o.x += s.x; o.y += s.y; o.z += s.z; o.w += s.w;
+          *reinterpret_cast<float4*>(dst) = o;
+        } else {
+          if (col + 0 < M) dst[0] += s.x;
+          if (col + 1 < M) dst[1] += s.y;
+          if (col + 2 < M) dst[2] += s.z;
+          if (col + 3 < M) dst[3] += s.w;
+        }
       }
       float* d = st + lr * 129 + 4 * c4;
       d[0] = s.x; d[1] = s.y; d[2] = s.z; d[3] = s.w;
     }
     __syncthreads();
     if (bi != bj) {
-      // transpose: target row n0 + lc, target columns m0 + sb*32 + (0..31)
+      // transpose: target row n0 + lc, target columns m0 + sb*32 + (0..31); the sixteen old
+      // values of a thread are loaded before its first store
       const int lr = tid & 31;
-      for (int lc = tid >> 5; lc < TILE; lc += 8) {
-        int64_t row = n0 + lc;
-        int64_t col = m0 + sb * 32 + lr;
-        if (row < M && col < M) C[row * ldc + col] += st[lr * 129 + lc];
+      const int64_t col = m0 + sb * 32 + lr;
+      float oldv[TILE / 8];
+#pragma unroll
+      for (int q = 0; q < TILE / 8; ++q) {
+        const int64_t row = n0 + (tid >> 5) + 8 * q;
+        oldv[q] = (row < M && col < M) ? C[row * ldc + col] : 0.0f;
+      }
+#pragma unroll
+      for (int q = 0; q < TILE / 8; ++q) {
+        const int lc = (tid >> 5) + 8 * q;
+        const int64_t row = n0 + lc;
+        if (row < M && col < M) C[row * ldc + col] = oldv[q] + st[lr * 129 + lc];
       }
     }
     __syncthreads();
