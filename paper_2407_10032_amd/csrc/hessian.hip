@@ -11,9 +11,9 @@
 
 namespace {
 
-constexpr int KT = 32;                       // tokens per LDS stage (64 KB of LDS, two workgroups per CU;
-                                             // 16-token stages at four per CU measured 2 % slower)
-constexpr int MINW = 2;
+constexpr int KT = 16;                       // tokens per LDS stage: 32 KB of LDS and <= 168 registers put
+constexpr int MINW = 3;                      // three workgroups on a CU (1.4 % faster than 32-token
+                                             // stages at two per CU; four per CU is slower again)
 constexpr int MAX_SPLITS = 64;
 
 struct HessianPlan {
@@ -28,16 +28,16 @@ struct HessianPlan {
 // a shorter tail at the end of the launch, but a larger share of each workgroup spent on its
 // first loads and its partial-tile store, and more partial tiles for the reduce kernel to
 // read.  The number of slices is the one that minimizes a small time model of these three
-// effects (constants measured on MI355X: 3.56 us per 32-token stage of a workgroup that
-// shares its compute unit with a second one, about 6 us of fixed cost per workgroup, half a
-// round of tail once the launch exceeds the resident slots, 3 TB/s for the reduce kernel).
+// effects (constants measured on MI355X: 2.67 us per 16-token stage of a workgroup that
+// shares its compute unit with two others, about 6 us of fixed cost per workgroup, half a
+// round of tail unless the workgroups fill a whole number of rounds, 3 TB/s for the reduce kernel).
 HessianPlan make_plan(int64_t c, int64_t n_tokens) {
   HessianPlan p;
   p.T = (int)lq::ceil_div(c, lq::TILE);
   p.ntiles = p.T * (p.T + 1) / 2;
   const int64_t n = n_tokens > 0 ? n_tokens : 1;
-  const double slots = 512.0;                  // 256 compute units x 2 resident workgroups
-  const double stage_us = 3.56, fixed_us = 6.0;
+  const double slots = 256.0 * MINW;           // compute units x resident workgroups
+  const double stage_us = 2.67, fixed_us = 6.0;
   int best_s = 1;
   double best_t = 0.0;
   for (int s = 1; s <= MAX_SPLITS; ++s) {
@@ -46,7 +46,10 @@ HessianPlan make_plan(int64_t c, int64_t n_tokens) {
     if (used != s) continue;                   // the same slicing as a smaller s
     const double stages = (double)per / KT;
     const double wgs = (double)p.ntiles * (double)used;
-    const double rounds = wgs <= slots ? 1.0 : wgs / slots + 0.5;
+    // equal workgroups in a whole number of rounds end nearly together (a quarter round of
+    // drift); otherwise the last round is partly empty and costs about half a round
+    const bool whole = ((int64_t)wgs % (int64_t)slots) == 0;
+    const double rounds = wgs <= slots ? 1.0 : wgs / slots + (whole ? 0.25 : 0.5);
     const double t_main = rounds * (stages * stage_us + fixed_us);
     const double t_reduce = wgs * (lq::TILE * lq::TILE * 4.0) / 3.0e6;   // bytes / (3 TB/s) in us
     const double t = t_main + t_reduce;
