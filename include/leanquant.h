@@ -182,7 +182,9 @@ lq_status lq_unpack_layer(const uint8_t* packed, int64_t packed_ld, const uint16
                           void* stream);
 
 /* Scratch bytes a call needs (host-only computation).  n_tokens is used by
- * LQ_CALL_HESSIAN only; r by FIT_GRID/QUANTIZE; P may be NULL for HESSIAN/CHOLESKY. */
+ * LQ_CALL_HESSIAN only; r by FIT_GRID/QUANTIZE; P may be NULL for HESSIAN/CHOLESKY.
+ * For LQ_CALL_HESSIAN the size depends on how the token range is cut and is NOT monotonic in
+ * n_tokens: a workspace shared by calls with different chunk sizes must cover the maximum. */
 size_t lq_workspace_bytes(int which_call, int64_t r, int64_t c, int64_t n_tokens, const lq_params* P);
 
 /* Text of the last error on the calling thread ("" if none).  Never NULL.  Host pointer. */
