@@ -28,7 +28,7 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 # HBM-side bytes of one Gram-kernel launch on the c2 workload, from the two rocprofv3 --pmc
 # runs (FETCH_SIZE, WRITE_SIZE, each scaled by a plain copy of known size) summarised in
 # profiles/bench_c2_gram_kernel_counters.md.  Only valid for that workload.
-GRAM_TRAFFIC_BYTES_C2 = 69.8e9
+GRAM_TRAFFIC_BYTES_C2 = 80.1e9
 
 
 def log(msg):
