@@ -352,3 +352,73 @@ def obs_fixed_order(W, Hd, quant_col):
         Hinv[:, j] = 0.0
         Hinv[j, j] = 1.0                                    # placeholder, never used again
     return What, eps
+
+
+# --------------------------------------------------------------------------
+# LeanQuant-Exact (Algorithm 2 of the appendix): greedy order, explicit inverse
+# --------------------------------------------------------------------------
+def exact_row(w, Hinv, quant):
+    """Algorithm 2's loop for one row.
+
+    w [c]; Hinv [c x c] the inverse Hessian the row starts from; quant(w_vec) ->
+    (quantized values, codes) on the row's fixed grid.  In each of the c steps the
+    not yet quantized weight with the smallest loss error (quant(w_i) - w_i)^2 /
+    (2 Hinv_ii) (Eq. 3) is quantized (ties: lowest index), the other weights move by
+    -Hinv[:, i] / Hinv_ii (w_i - w_hat_i), and row and column i leave the inverse
+    (Eq. 9).  Returns (w_hat, codes, order, eps) with eps the summed loss error.
+    """
+    w = np.array(w, dtype=F64, copy=True)
+    Hinv = np.array(Hinv, dtype=F64, copy=True)
+    c = w.size
+    w_hat = np.zeros(c, dtype=F64)
+    codes = np.zeros(c, dtype=np.int64)
+    live = np.ones(c, dtype=bool)
+    order = []
+    eps = 0.0
+    for _ in range(c):
+        q, code = quant(w)
+        score = np.where(live, (q - w) ** 2 / (2.0 * np.where(live, np.diag(Hinv), 1.0)), np.inf)
+        i = int(np.argmin(score))                     # first minimum = lowest index
+        order.append(i)
+        eps += score[i]
+        w_hat[i] = q[i]
+        codes[i] = code[i]
+        hii = Hinv[i, i]
+        col = Hinv[:, i].copy()
+        w = w - col / hii * (w[i] - q[i])
+        Hinv = Hinv - np.outer(col, Hinv[i, :]) / hii
+        Hinv[i, :] = 0.0
+        Hinv[:, i] = 0.0
+        live[i] = False
+        w[i] = q[i]
+    return w_hat, codes, np.array(order), eps
+
+
+def leanquant_exact(W, H, mode, bits, df=0.01, p=4.0, T=2048, t=None, max_iter=100):
+    """Algorithm 2 for every row of W from an accumulated H.
+
+    Readings: the inverse is the damped one, as in Algorithm 1 (Algorithm 2 writes
+    (2 X X^T)^-1; Section 2.2's dampening is what keeps it invertible); the grid is
+    learned once from the original row (lines 3-7 precede the loop); the affine grid is
+    one (S, Z) per row.  Returns dict with grid, W_hat, codes, order, eps.
+    """
+    W = np.atleast_2d(np.asarray(W, dtype=F64))
+    Hinv = np.linalg.inv(dampen(H, df))
+    d = np.diag(Hinv).copy()
+    r, c = W.shape
+    if mode == "nu":
+        grid = fit_grid_nu(W, d, bits, p, max_iter=max_iter)
+    else:
+        grid = fit_grid_aff(W, d, bits, p, group_size=0, T=T, t=t)
+    What = np.zeros((r, c))
+    codes = np.zeros((r, c), dtype=np.int64)
+    order = np.zeros((r, c), dtype=np.int64)
+    eps = np.zeros(r)
+    for k in range(r):
+        if mode == "nu":
+            quant = lambda v, G=grid[k]: quant_nu(v, G)
+        else:
+            S, Z = grid[k, 0, 0], grid[k, 0, 1]
+            quant = lambda v, S=S, Z=Z: quant_aff(v, S, Z, bits)
+        What[k], codes[k], order[k], eps[k] = exact_row(W[k], Hinv, quant)
+    return dict(grid=grid, W_hat=What, codes=codes, order=order, eps=eps, Hinv=Hinv, d=d)
