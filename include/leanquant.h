@@ -55,7 +55,8 @@ typedef enum {
   LQ_CALL_HESSIAN = 0,
   LQ_CALL_CHOLESKY = 1,
   LQ_CALL_FIT_GRID = 2,
-  LQ_CALL_QUANTIZE = 3
+  LQ_CALL_QUANTIZE = 3,
+  LQ_CALL_EXACT = 4
 } lq_call;
 
 /* Inputs of Algorithm 1 other than W and X, plus the grid-search constants. */
@@ -156,6 +157,33 @@ lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t ldw, const f
                             void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Algorithm 2 of the appendix (LeanQuant-Exact, for small networks): per row, in each of c
+ * steps the not yet quantized weight with the smallest loss error (quant(w_i) - w_i)^2 /
+ * (2 Hinv_ii) (Eq. 3) is quantized (ties: lowest index), the others move by
+ * -Hinv[:, i] / Hinv_ii (w_i - w_hat_i), and row and column i leave the inverse (Eq. 9).
+ * O(r c^3) and all in fp64; c <= 2048.
+ *   W        [r x c] (ldw) in/out: on return the quantized rows W_hat.
+ *   Hinv     [c x c] (ldh) DOUBLE, the symmetric damped inverse Hessian every row starts from,
+ *            read only; lq_hinv_from_factor forms it as U^T U from lq_cholesky_inv's factor.
+ *   grid     as written by lq_fit_grid for the same P (learned once from the original rows,
+ *            lines 3-7 of Algorithm 2); affine mode takes one (S, Z) per row: group_size 0.
+ *   codes    [r x c] uint8 out (leading dimension c).
+ *   order    [r x c] int32 out or NULL: the index quantized at each step.
+ *   row_loss [r] out or NULL: the summed loss errors of the row.
+ *   ws       LQ_CALL_EXACT scratch: one c x c double matrix per resident workgroup
+ *            (min(r, 512) of them).
+ */
+lq_status lq_quantize_exact(float* W, int64_t r, int64_t c, int64_t ldw, const double* Hinv,
+                            int64_t ldh, const float* grid, const lq_params* P, uint8_t* codes,
+                            int32_t* order, float* row_loss, void* ws, size_t ws_bytes, void* stream);
+
+/* Hinv = U^T U in fp64 from the fp32 upper factor U [c x c] (ldu) of lq_cholesky_inv.
+ * Hinv [c x c] (ldh) double out.  O(c^3) on the vector units: meant for the small c of
+ * lq_quantize_exact. */
+lq_status lq_hinv_from_factor(const float* U, int64_t ldu, int64_t c, double* Hinv, int64_t ldh,
+                              void* stream);
+
+/*
  * Stored form of a quantized layer.  The "Bits" columns of the paper's result tables count b
  * bits per weight plus sixteen bits per grid point per row (non-uniform grids: one set of 2^b
  * points per row, Section 2.1) or per scale and per zero-point of a group (affine grids):
@@ -182,7 +210,7 @@ lq_status lq_unpack_layer(const uint8_t* packed, int64_t packed_ld, const uint16
                           void* stream);
 
 /* Scratch bytes a call needs (host-only computation).  n_tokens is used by
- * LQ_CALL_HESSIAN only; r by FIT_GRID/QUANTIZE; P may be NULL for HESSIAN/CHOLESKY.
+ * LQ_CALL_HESSIAN only; r by FIT_GRID/QUANTIZE/EXACT; P may be NULL for HESSIAN/CHOLESKY/EXACT.
  * For LQ_CALL_HESSIAN the size depends on how the token range is cut and is NOT monotonic in
  * n_tokens: a workspace shared by calls with different chunk sizes must cover the maximum. */
 size_t lq_workspace_bytes(int which_call, int64_t r, int64_t c, int64_t n_tokens, const lq_params* P);

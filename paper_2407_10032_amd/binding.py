@@ -19,10 +19,10 @@ LIB_PATH = os.path.join(_HERE, "libleanquant.so")
 
 LQ_OK, LQ_ERR_INVALID_ARG, LQ_ERR_NOT_PD, LQ_ERR_UNSUPPORTED, LQ_ERR_WORKSPACE, LQ_ERR_HIP = range(6)
 LQ_GRID_NONUNIFORM, LQ_GRID_AFFINE = 0, 1
-LQ_CALL_HESSIAN, LQ_CALL_CHOLESKY, LQ_CALL_FIT_GRID, LQ_CALL_QUANTIZE = range(4)
+LQ_CALL_HESSIAN, LQ_CALL_CHOLESKY, LQ_CALL_FIT_GRID, LQ_CALL_QUANTIZE, LQ_CALL_EXACT = range(5)
 
 EXPORTS = ("lq_params_default", "lq_hessian_accumulate", "lq_cholesky_inv", "lq_fit_grid",
-           "lq_fit_grid_from", "lq_quantize_layer", "lq_packed_row_bytes", "lq_bits_per_weight", "lq_pack_layer",
+           "lq_fit_grid_from", "lq_quantize_layer", "lq_quantize_exact", "lq_hinv_from_factor", "lq_packed_row_bytes", "lq_bits_per_weight", "lq_pack_layer",
            "lq_unpack_layer", "lq_workspace_bytes", "lq_last_error", "lq_version")
 
 
@@ -65,6 +65,10 @@ def load() -> ctypes.CDLL:
     lib.lq_fit_grid_from.restype = ctypes.c_int
     lib.lq_quantize_layer.argtypes = [vp, i64, i64, i64, vp, i64, vp, pp, vp, vp, vp, sz, vp]
     lib.lq_quantize_layer.restype = ctypes.c_int
+    lib.lq_quantize_exact.argtypes = [vp, i64, i64, i64, vp, i64, vp, pp, vp, vp, vp, vp, sz, vp]
+    lib.lq_quantize_exact.restype = ctypes.c_int
+    lib.lq_hinv_from_factor.argtypes = [vp, i64, i64, vp, i64, vp]
+    lib.lq_hinv_from_factor.restype = ctypes.c_int
     lib.lq_packed_row_bytes.argtypes = [i64, ctypes.c_int32]
     lib.lq_packed_row_bytes.restype = i64
     lib.lq_bits_per_weight.argtypes = [i64, i64, pp]
@@ -185,6 +189,24 @@ def lq_quantize_layer(W: torch.Tensor, U: torch.Tensor, grid: torch.Tensor, P: l
                                     _ptr(grid, torch.float32, "grid"), ctypes.byref(P),
                                     _ptr(codes, torch.uint8, "codes"),
                                     _ptr(row_loss, torch.float32, "row_loss"), wp, wn, _stream()))
+
+
+def lq_quantize_exact(W: torch.Tensor, Hinv: torch.Tensor, grid: torch.Tensor, P: lq_params,
+                      codes: torch.Tensor, order: Optional[torch.Tensor],
+                      row_loss: Optional[torch.Tensor], ws: torch.Tensor) -> None:
+    r, c = W.shape
+    wp, wn = _ws(ws)
+    _check(load().lq_quantize_exact(_ptr(W, torch.float32, "W"), r, c, _ld(W, "W"),
+                                    _ptr(Hinv, torch.float64, "Hinv"), _ld(Hinv, "Hinv"),
+                                    _ptr(grid, torch.float32, "grid"), ctypes.byref(P),
+                                    _ptr(codes, torch.uint8, "codes"), _ptr(order, torch.int32, "order"),
+                                    _ptr(row_loss, torch.float32, "row_loss"), wp, wn, _stream()))
+
+
+def lq_hinv_from_factor(U: torch.Tensor, Hinv: torch.Tensor) -> None:
+    c = U.shape[0]
+    _check(load().lq_hinv_from_factor(_ptr(U, torch.float32, "U"), _ld(U, "U"), c,
+                                      _ptr(Hinv, torch.float64, "Hinv"), _ld(Hinv, "Hinv"), _stream()))
 
 
 def lq_packed_row_bytes(c: int, bits: int) -> int:

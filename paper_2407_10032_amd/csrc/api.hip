@@ -10,6 +10,7 @@ size_t hessian_workspace_bytes(int64_t c, int64_t n_tokens);
 size_t cholesky_workspace_bytes(int64_t c);
 size_t fit_grid_workspace_bytes(int64_t c);
 size_t quantize_workspace_bytes(int64_t r, int64_t c, int block);
+size_t exact_workspace_bytes(int64_t r, int64_t c);
 
 char* error_buffer() {
   static thread_local char buf[512] = {0};
@@ -96,6 +97,7 @@ extern "C" size_t lq_workspace_bytes(int which_call, int64_t r, int64_t c, int64
     case LQ_CALL_CHOLESKY: return lq::cholesky_workspace_bytes(c);
     case LQ_CALL_FIT_GRID: return lq::fit_grid_workspace_bytes(c);
     case LQ_CALL_QUANTIZE: return lq::quantize_workspace_bytes(r, c, P ? P->block : 128);
+    case LQ_CALL_EXACT: return lq::exact_workspace_bytes(r, c);
     default: return 0;
   }
 }
