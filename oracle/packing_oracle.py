@@ -99,3 +99,11 @@ def dequantize(packed, table, c, bits, mode, group_size=0):
     Z = table[..., 1].copy().view(np.int16).astype(np.float64)
     gi = np.arange(c) // g
     return ((codes - Z[:, gi]) * S[:, gi]).astype(np.float32)
+
+
+def matvec_packed(packed, table, X, c, bits, mode, group_size=0):
+    """Y[n, k] = sum_j W_hat[k, j] X[n, j] with W_hat the weights the stored form stands for
+    (dequantize above), in float64.  X [nb x c]; returns [nb x r]: what the inference kernel
+    of a quantized linear layer computes (the paper's appendix on inference efficiency)."""
+    Wh = dequantize(packed, table, c, bits, mode, group_size).astype(np.float64)
+    return np.asarray(X, dtype=np.float64) @ Wh.T

@@ -100,3 +100,16 @@ def test_dequantize_follows_the_grid_definitions():
     w = po.dequantize(po.pack_codes(codes, 4), po.table_aff(np.stack([S, Z], -1)), 8, 4, "aff", 4)
     gi = np.arange(8) // 4
     assert np.array_equal(w, ((codes - Z[:, gi]) * S[:, gi]).astype(np.float32))
+
+
+def test_matvec_packed_is_the_product_with_the_dequantized_weights():
+    rng = np.random.default_rng(9)
+    # identity-like check: a grid that is exact in binary16 and one-hot inputs read out columns
+    grid = np.sort(rng.integers(-512, 512, size=(5, 4)) / 1024.0, axis=1)
+    codes = rng.integers(0, 4, size=(5, 12))
+    packed, table = po.pack_codes(codes, 2), po.table_nu(grid)
+    W = np.take_along_axis(grid, codes, axis=1)
+    Y = po.matvec_packed(packed, table, np.eye(12), 12, 2, "nu")
+    assert np.array_equal(Y, W.T)
+    x = rng.standard_normal((3, 12))
+    assert np.allclose(po.matvec_packed(packed, table, x, 12, 2, "nu"), x @ W.T, rtol=0, atol=1e-15)
