@@ -209,6 +209,20 @@ lq_status lq_unpack_layer(const uint8_t* packed, int64_t packed_ld, const uint16
                           int64_t c, const lq_params* P, float* W_hat, int64_t ldw, uint8_t* codes,
                           void* stream);
 
+/*
+ * Product with a stored layer, as a quantized linear layer does when decoding (the paper's
+ * appendix on inference efficiency): Y[n][k] = sum_j W_hat[k][j] X[n][j] with W_hat the
+ * weights the stored form stands for (see lq_unpack_layer), fp32 accumulation.
+ *   packed, table  as written by lq_pack_layer for the same P; packed rows 16 / 4 / 8-byte
+ *                  aligned for 4 / 3 / 2 bits (base pointer and packed_ld).
+ *   X  [nb x c] fp32, rows contiguous, 16-byte aligned;  Y [nb x r] fp32 out.
+ * The codes are read once per input vector (nb passes).  Limits: c a multiple of 32 and at
+ * most 16384; affine groups multiples of 32 columns.  No workspace.
+ */
+lq_status lq_matvec_packed(const uint8_t* packed, int64_t packed_ld, const uint16_t* table, int64_t r,
+                           int64_t c, const lq_params* P, const float* X, int64_t nb, float* Y,
+                           void* stream);
+
 /* Scratch bytes a call needs (host-only computation).  n_tokens is used by
  * LQ_CALL_HESSIAN only; r by FIT_GRID/QUANTIZE/EXACT; P may be NULL for HESSIAN/CHOLESKY/EXACT.
  * For LQ_CALL_HESSIAN the size depends on how the token range is cut and is NOT monotonic in
