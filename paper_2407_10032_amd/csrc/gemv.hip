@@ -60,6 +60,30 @@ __device__ __forceinline__ void unit_fma(const uint32_t (&w)[BITS], const float 
   }
 }
 
+// Affine grids at 2 and 4 bits: sum_j code_j x_j of a unit with the codes spread to one per
+// byte by a mask (one mask per 4 codes), so that the byte-to-float conversion does the
+// extraction: two instructions per weight instead of three.
+template <int BITS>
+__device__ __forceinline__ float unit_dot_bytes(const uint32_t (&w)[BITS], const float (&x)[UNIT]) {
+  static_assert(BITS == 2 || BITS == 4, "codes that do not straddle bytes");
+  constexpr int PER_BYTE = 8 / BITS;                 // codes per byte
+  constexpr int PER_WORD = 32 / BITS;
+  constexpr uint32_t MASK = ((1u << BITS) - 1u) * 0x01010101u;
+  float dot = 0.0f;
+#pragma unroll
+  for (int i = 0; i < BITS; ++i) {
+#pragma unroll
+    for (int s = 0; s < PER_BYTE; ++s) {
+      uint32_t m = (w[i] >> (BITS * s)) & MASK;        // byte b holds code PER_BYTE * b + s of the word
+      asm volatile("" : "+v"(m));                      // keep the mask: the compiler would go back to bit-field extracts
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+        dot = fmaf((float)((m >> (8 * b)) & 0xffu), x[PER_WORD * i + PER_BYTE * b + s], dot);
+    }
+  }
+  return dot;
+}
+
 // RB rows per workgroup: 16 for layers with many rows (the input vector is re-read per
 // workgroup), 8 where that leaves too few workgroups to fill the chip.
 template <int BITS, bool AFF, int U, int RB>
@@ -72,17 +96,55 @@ __global__ __launch_bounds__(NT) void matvec_packed_kernel(MvArgs a) {
   const int64_t row0 = (int64_t)blockIdx.x * RB;
   const int nunits = a.c / UNIT;
 
-  // this lane's columns of x, and their sums (affine: the zero-point term).  Units past the
-  // end of the row read the row's last unit and count as zero (no divergent branches).
-  float x[U][UNIT];
-  float xsum[U];
+  // Units past the end of the row read the row's last unit and count as zero, rows past r
+  // read row r - 1 and are discarded: no divergent branches around the loads.
   bool uval[U];
-  int uidx[U];
+  int uidx[U], gidx[U];
 #pragma unroll
   for (int i = 0; i < U; ++i) {
     const int u = tid + i * NT;
     uval[i] = u < nunits;
     uidx[i] = uval[i] ? u : nunits - 1;
+    gidx[i] = AFF ? (uidx[i] * UNIT) / a.group : 0;
+  }
+
+  // Rows in batches of RG, double buffered: the loads of the next batch are in flight while
+  // the current one is looked up and accumulated.
+  constexpr int RG = 4 / U;
+  static_assert(RB % (2 * RG) == 0, "row batches");
+  auto load_batch = [&](int rb0, uint32_t (&w)[RG][U][BITS], uint32_t (&sz)[RG][U]) {
+#pragma unroll
+    for (int q = 0; q < RG; ++q) {
+      int64_t row = row0 + rb0 + q;
+      row = row < a.r ? row : a.r - 1;
+#pragma unroll
+      for (int i = 0; i < U; ++i) {
+        load_unit<BITS>(a.packed + row * a.packed_ld + (int64_t)uidx[i] * UB, w[q][i]);
+        // affine: binary16 S | int16 Z << 16 of the unit's group
+        if (AFF) sz[q][i] = *reinterpret_cast<const uint32_t*>(a.table + (row * a.ngroups + gidx[i]) * 2);
+        if (!uval[i]) {
+#pragma unroll
+          for (int b = 0; b < BITS; ++b) w[q][i][b] = 0u;
+        }
+      }
+    }
+  };
+  // everything the first batch needs is requested at once: codes, tables, x
+  uint32_t wa[RG][U][BITS], wb[RG][U][BITS];
+  uint32_t sa[RG][U], sb[RG][U];
+  load_batch(0, wa, sa);
+  static_assert(RB * K <= NT, "one table entry per thread");
+  uint16_t tab = 0;
+  if (!AFF && tid < RB * K) {
+    int64_t row = row0 + tid / K;
+    row = row < a.r ? row : a.r - 1;
+    tab = a.table[row * K + tid % K];
+  }
+  // this lane's columns of x, and their sums (affine: the zero-point term)
+  float x[U][UNIT];
+  float xsum[U];
+#pragma unroll
+  for (int i = 0; i < U; ++i) {
     xsum[i] = 0.0f;
 #pragma unroll
     for (int q4 = 0; q4 < UNIT / 4; ++q4) {
@@ -92,34 +154,10 @@ __global__ __launch_bounds__(NT) void matvec_packed_kernel(MvArgs a) {
       xsum[i] += (v.x + v.y) + (v.z + v.w);
     }
   }
-  if (!AFF) {
-    for (int f = tid; f < RB * K; f += NT) {
-      const int rb = f / K, m = f - rb * K;
-      sLut[rb][m] = (row0 + rb < a.r) ? __half2float(__ushort_as_half(a.table[(row0 + rb) * K + m])) : 0.0f;
-    }
-  }
+  if (!AFF && tid < RB * K) sLut[tid / K][tid % K] = __half2float(__ushort_as_half(tab));
   __syncthreads();
 
-  // Rows in batches of RG, double buffered: the loads of the next batch are in flight while
-  // the current one is looked up and accumulated.  Rows past r read row r - 1 (discarded).
-  constexpr int RG = 2;
-  static_assert(RB % (2 * RG) == 0, "row batches");
-  auto load_batch = [&](int rb0, uint32_t (&w)[RG][U][BITS]) {
-#pragma unroll
-    for (int q = 0; q < RG; ++q) {
-      int64_t row = row0 + rb0 + q;
-      row = row < a.r ? row : a.r - 1;
-#pragma unroll
-      for (int i = 0; i < U; ++i) {
-        load_unit<BITS>(a.packed + row * a.packed_ld + (int64_t)uidx[i] * UB, w[q][i]);
-        if (!uval[i]) {
-#pragma unroll
-          for (int b = 0; b < BITS; ++b) w[q][i][b] = 0u;
-        }
-      }
-    }
-  };
-  auto use_batch = [&](int rb0, const uint32_t (&w)[RG][U][BITS]) {
+  auto use_batch = [&](int rb0, const uint32_t (&w)[RG][U][BITS], const uint32_t (&sz)[RG][U]) {
 #pragma unroll
     for (int q = 0; q < RG; ++q) {
       const int rb = rb0 + q;
@@ -130,11 +168,11 @@ __global__ __launch_bounds__(NT) void matvec_packed_kernel(MvArgs a) {
       for (int i = 0; i < U; ++i) {
         if (AFF) {
           // Section 2.1: (w_int - Z) S, with the unit's group pair: S (sum code x - Z sum x)
-          const uint16_t* sz = a.table + (row * a.ngroups + (uidx[i] * UNIT) / a.group) * 2;
-          const float S = __half2float(__ushort_as_half(sz[0]));
-          const float Z = (float)(int16_t)sz[1];
+          const float S = __half2float(__ushort_as_half((uint16_t)(sz[q][i] & 0xffffu)));
+          const float Z = (float)(int16_t)(sz[q][i] >> 16);
           float dot = 0.0f;
-          unit_fma<BITS, true, 0>(w[q][i], x[i], nullptr, dot);
+          if constexpr (BITS == 3) unit_fma<BITS, true, 0>(w[q][i], x[i], nullptr, dot);
+          else dot = unit_dot_bytes<BITS>(w[q][i], x[i]);
           acc = fmaf(S, dot - Z * xsum[i], acc);
         } else {
           unit_fma<BITS, false, 0>(w[q][i], x[i], sLut[rb], acc);
@@ -145,14 +183,12 @@ __global__ __launch_bounds__(NT) void matvec_packed_kernel(MvArgs a) {
       if (lane == 0) sPart[rb][wave] = acc;
     }
   };
-  uint32_t wa[RG][U][BITS], wb[RG][U][BITS];
-  load_batch(0, wa);
 #pragma unroll
   for (int rb0 = 0; rb0 < RB; rb0 += 2 * RG) {
-    load_batch(rb0 + RG, wb);
-    use_batch(rb0, wa);
-    if (rb0 + 2 * RG < RB) load_batch(rb0 + 2 * RG, wa);
-    use_batch(rb0 + RG, wb);
+    load_batch(rb0 + RG, wb, sb);
+    use_batch(rb0, wa, sa);
+    if (rb0 + 2 * RG < RB) load_batch(rb0 + 2 * RG, wa, sa);
+    use_batch(rb0 + RG, wb, sb);
   }
   __syncthreads();
   if (tid < RB && row0 + tid < a.r) {
