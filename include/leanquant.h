@@ -94,6 +94,30 @@ lq_status lq_hessian_accumulate(float* H, int64_t ldh, const float* X, int64_t n
                                 int64_t ldx, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The same accumulation (Algorithm 1 line 3) for calibration activations that still sit in
+ * HOST memory: X_host is cut into chunks of chunk_tokens rows; chunk k + 1 is copied to the
+ * device on an internal copy stream while chunk k is accumulated on `stream` (two staging
+ * buffers in ws).  The result is bit-identical to one lq_hessian_accumulate call per chunk.
+ *   H         device [c x c] (ldh), as above; zero-filled by the caller before the first call.
+ *   X_host    HOST pointer, [n_tokens x c] with leading dimension ldx >= c.  Read only; must
+ *             stay valid and unchanged until the work enqueued on `stream` has finished.
+ *             Page-locked memory (hipHostMalloc, or a pinned tensor) lets the copies overlap
+ *             the kernels; with pageable memory the call is still correct but the copies
+ *             block the host.
+ *   chunk_tokens >= 1: rows per chunk (8192 - 32768 are sensible).
+ *   ws        device scratch of lq_hessian_host_workspace_bytes(c, n_tokens, chunk_tokens)
+ *             bytes, 256-byte aligned.
+ * The call returns after enqueueing (with page-locked X_host); errors as lq_hessian_accumulate.
+ */
+lq_status lq_hessian_accumulate_host(float* H, int64_t ldh, const float* X_host, int64_t n_tokens,
+                                     int64_t c, int64_t ldx, int64_t chunk_tokens, void* ws,
+                                     size_t ws_bytes, void* stream);
+
+/* Scratch size of lq_hessian_accumulate_host (partial sums + two chunk buffers); 0 for
+ * invalid arguments.  Host function. */
+size_t lq_hessian_host_workspace_bytes(int64_t c, int64_t n_tokens, int64_t chunk_tokens);
+
+/*
  * Algorithm 1 line 4: dampen, invert, factor.
  *   H         [c x c] (ldh), symmetric, read only.
  *   damp      df; lambda = df * mean(diag H) is added to the diagonal.

@@ -21,7 +21,8 @@ LQ_OK, LQ_ERR_INVALID_ARG, LQ_ERR_NOT_PD, LQ_ERR_UNSUPPORTED, LQ_ERR_WORKSPACE, 
 LQ_GRID_NONUNIFORM, LQ_GRID_AFFINE = 0, 1
 LQ_CALL_HESSIAN, LQ_CALL_CHOLESKY, LQ_CALL_FIT_GRID, LQ_CALL_QUANTIZE, LQ_CALL_EXACT = range(5)
 
-EXPORTS = ("lq_params_default", "lq_hessian_accumulate", "lq_cholesky_inv", "lq_fit_grid",
+EXPORTS = ("lq_params_default", "lq_hessian_accumulate", "lq_hessian_accumulate_host",
+           "lq_hessian_host_workspace_bytes", "lq_cholesky_inv", "lq_fit_grid",
            "lq_fit_grid_from", "lq_quantize_layer", "lq_quantize_exact", "lq_hinv_from_factor", "lq_packed_row_bytes", "lq_bits_per_weight", "lq_pack_layer",
            "lq_unpack_layer", "lq_matvec_packed", "lq_workspace_bytes", "lq_last_error", "lq_version")
 
@@ -57,6 +58,10 @@ def load() -> ctypes.CDLL:
     lib.lq_params_default.restype = None
     lib.lq_hessian_accumulate.argtypes = [vp, i64, vp, i64, i64, i64, vp, sz, vp]
     lib.lq_hessian_accumulate.restype = ctypes.c_int
+    lib.lq_hessian_accumulate_host.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, sz, vp]
+    lib.lq_hessian_accumulate_host.restype = ctypes.c_int
+    lib.lq_hessian_host_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.lq_hessian_host_workspace_bytes.restype = sz
     lib.lq_cholesky_inv.argtypes = [vp, i64, i64, fp, vp, i64, vp, vp, vp, sz, vp]
     lib.lq_cholesky_inv.restype = ctypes.c_int
     lib.lq_fit_grid.argtypes = [vp, i64, i64, i64, vp, pp, vp, vp, sz, vp]
@@ -149,6 +154,23 @@ def lq_hessian_accumulate(H: torch.Tensor, X: torch.Tensor, ws: torch.Tensor) ->
     _check(load().lq_hessian_accumulate(_ptr(H, torch.float32, "H"), _ld(H, "H"),
                                         _ptr(X, torch.float32, "X"), X.shape[0], c, _ld(X, "X"),
                                         wp, wn, _stream()))
+
+
+def lq_hessian_host_workspace_bytes(c: int, n_tokens: int, chunk_tokens: int) -> int:
+    return int(load().lq_hessian_host_workspace_bytes(c, n_tokens, chunk_tokens))
+
+
+def lq_hessian_accumulate_host(H: torch.Tensor, X_host: torch.Tensor, chunk_tokens: int,
+                               ws: torch.Tensor) -> None:
+    """H += 2 X^T X with X [n_tokens x c] fp32 in host memory (pinned for overlap); the
+    tensor must stay alive and unchanged until the current stream has finished."""
+    c = H.shape[0]
+    if X_host.is_cuda or X_host.dtype != torch.float32:
+        raise TypeError("X_host must be a float32 CPU tensor")
+    wp, wn = _ws(ws)
+    _check(load().lq_hessian_accumulate_host(_ptr(H, torch.float32, "H"), _ld(H, "H"),
+                                             X_host.data_ptr(), X_host.shape[0], c, _ld(X_host, "X_host"),
+                                             int(chunk_tokens), wp, wn, _stream()))
 
 
 def lq_cholesky_inv(H: torch.Tensor, damp: float, U: torch.Tensor, hinv_diag: torch.Tensor,

@@ -68,9 +68,9 @@ namespace lq {
 size_t hessian_workspace_bytes(int64_t c, int64_t n_tokens) { return make_plan(c, n_tokens).ws_bytes; }
 }  // namespace lq
 
-extern "C" lq_status lq_hessian_accumulate(float* H, int64_t ldh, const float* X, int64_t n_tokens,
-                                           int64_t c, int64_t ldx, void* ws, size_t ws_bytes,
-                                           void* stream) {
+static lq_status accumulate_device(float* H, int64_t ldh, const float* X, int64_t n_tokens,
+                                   int64_t c, int64_t ldx, void* ws, size_t ws_bytes,
+                                   hipStream_t st) {
   if (!H || (!X && n_tokens > 0)) return lq::fail(LQ_ERR_INVALID_ARG, "lq_hessian_accumulate: null pointer");
   if (c < 1 || n_tokens < 0) return lq::fail(LQ_ERR_INVALID_ARG, "lq_hessian_accumulate: c=%lld n_tokens=%lld", (long long)c, (long long)n_tokens);
   if (ldh < c || ldx < c) return lq::fail(LQ_ERR_INVALID_ARG, "lq_hessian_accumulate: leading dimension smaller than c");
@@ -80,7 +80,6 @@ extern "C" lq_status lq_hessian_accumulate(float* H, int64_t ldh, const float* X
   if (!ws || !lq::aligned(ws, 256) || ws_bytes < plan.ws_bytes)
     return lq::fail(LQ_ERR_WORKSPACE, "lq_hessian_accumulate: workspace needs %zu bytes, 256-byte aligned", plan.ws_bytes);
 
-  hipStream_t st = (hipStream_t)stream;
   lq::TnGemmArgs a;
   a.P = X; a.ldp = ldx;
   a.Q = X; a.ldq = ldx;
@@ -112,5 +111,82 @@ extern "C" lq_status lq_hessian_accumulate(float* H, int64_t ldh, const float* X
   hipLaunchKernelGGL(lq::tn_reduce_sym_kernel, dim3(4 * plan.ntiles), block, 0, st, (const float*)ws,
                      plan.splits, plan.ntiles, plan.T, H, ldh, c, 2.0f);
   LQ_CHECK_LAUNCH("tn_reduce_sym_kernel");
+  return LQ_OK;
+}
+
+extern "C" lq_status lq_hessian_accumulate(float* H, int64_t ldh, const float* X, int64_t n_tokens,
+                                           int64_t c, int64_t ldx, void* ws, size_t ws_bytes,
+                                           void* stream) {
+  return accumulate_device(H, ldh, X, n_tokens, c, ldx, ws, ws_bytes, (hipStream_t)stream);
+}
+
+// Layout of the host-streaming call's workspace: the partial-sum scratch of the larger of the
+// two chunk sizes that occur (whole chunks and the tail), then two chunk buffers.
+namespace {
+struct HostPlan {
+  size_t partial_bytes;
+  size_t chunk_bytes;     // one staging buffer, 256-byte multiple
+  size_t total;
+};
+HostPlan make_host_plan(int64_t c, int64_t n_tokens, int64_t chunk_tokens) {
+  HostPlan hp;
+  const int64_t whole = n_tokens < chunk_tokens ? n_tokens : chunk_tokens;
+  const int64_t tail = n_tokens > chunk_tokens ? n_tokens % chunk_tokens : 0;
+  size_t part = make_plan(c, whole).ws_bytes;
+  if (tail > 0) { const size_t t = make_plan(c, tail).ws_bytes; part = t > part ? t : part; }
+  hp.partial_bytes = lq::align_up(part, 256);
+  hp.chunk_bytes = lq::align_up((size_t)whole * (size_t)c * sizeof(float), 256);
+  hp.total = hp.partial_bytes + 2 * hp.chunk_bytes;
+  return hp;
+}
+}  // namespace
+
+extern "C" size_t lq_hessian_host_workspace_bytes(int64_t c, int64_t n_tokens, int64_t chunk_tokens) {
+  if (c < 1 || n_tokens < 1 || chunk_tokens < 1) return 0;
+  return make_host_plan(c, n_tokens, chunk_tokens).total;
+}
+
+extern "C" lq_status lq_hessian_accumulate_host(float* H, int64_t ldh, const float* X_host,
+                                                int64_t n_tokens, int64_t c, int64_t ldx,
+                                                int64_t chunk_tokens, void* ws, size_t ws_bytes,
+                                                void* stream) {
+  if (!H || (!X_host && n_tokens > 0)) return lq::fail(LQ_ERR_INVALID_ARG, "lq_hessian_accumulate_host: null pointer");
+  if (c < 1 || n_tokens < 0 || chunk_tokens < 1)
+    return lq::fail(LQ_ERR_INVALID_ARG, "lq_hessian_accumulate_host: c=%lld n_tokens=%lld chunk_tokens=%lld",
+                    (long long)c, (long long)n_tokens, (long long)chunk_tokens);
+  if (ldh < c || ldx < c) return lq::fail(LQ_ERR_INVALID_ARG, "lq_hessian_accumulate_host: leading dimension smaller than c");
+  if (n_tokens == 0) return LQ_OK;
+  const HostPlan hp = make_host_plan(c, n_tokens, chunk_tokens);
+  if (!ws || !lq::aligned(ws, 256) || ws_bytes < hp.total)
+    return lq::fail(LQ_ERR_WORKSPACE, "lq_hessian_accumulate_host: workspace needs %zu bytes, 256-byte aligned", hp.total);
+  lq::SideStream* side = lq::side_stream(1);
+  if (!side) return lq::fail(LQ_ERR_HIP, "lq_hessian_accumulate_host: cannot create the copy stream");
+
+  hipStream_t st = (hipStream_t)stream;
+  char* base = (char*)ws;
+  float* buf[2] = {(float*)(base + hp.partial_bytes), (float*)(base + hp.partial_bytes + hp.chunk_bytes)};
+  // the copy stream starts after everything enqueued before this call (the workspace may be in use)
+  LQ_CHECK_HIP(hipEventRecord(side->fork[2], st));
+  LQ_CHECK_HIP(hipStreamWaitEvent(side->stream, side->fork[2], 0));
+  const int64_t nchunks = lq::ceil_div(n_tokens, chunk_tokens);
+  for (int64_t k = 0; k < nchunks; ++k) {
+    const int64_t t0 = k * chunk_tokens;
+    const int64_t nt = (n_tokens - t0) < chunk_tokens ? (n_tokens - t0) : chunk_tokens;
+    float* dst = buf[k & 1];
+    // chunk k overwrites the buffer of chunk k - 2: wait until that one is accumulated
+    if (k >= 2) LQ_CHECK_HIP(hipStreamWaitEvent(side->stream, side->fork[k & 1], 0));
+    // rows are packed on the device (leading dimension c)
+    if (ldx == c)
+      LQ_CHECK_HIP(hipMemcpyAsync(dst, X_host + t0 * ldx, (size_t)nt * (size_t)c * sizeof(float),
+                                  hipMemcpyHostToDevice, side->stream));
+    else
+      LQ_CHECK_HIP(hipMemcpy2DAsync(dst, (size_t)c * sizeof(float), X_host + t0 * ldx, (size_t)ldx * sizeof(float),
+                                    (size_t)c * sizeof(float), (size_t)nt, hipMemcpyHostToDevice, side->stream));
+    LQ_CHECK_HIP(hipEventRecord(side->join, side->stream));
+    LQ_CHECK_HIP(hipStreamWaitEvent(st, side->join, 0));
+    lq_status rc = accumulate_device(H, ldh, dst, nt, c, c, base, hp.partial_bytes, st);
+    if (rc != LQ_OK) return rc;
+    if (k + 2 < nchunks) LQ_CHECK_HIP(hipEventRecord(side->fork[k & 1], st));
+  }
   return LQ_OK;
 }

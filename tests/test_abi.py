@@ -57,6 +57,11 @@ def test_argument_errors_are_host_side(lib):
     assert lib.lq_hessian_accumulate(dummy, 8, dummy, 4, 8, 8, None, 0, None) == lq.LQ_ERR_WORKSPACE
     assert lib.lq_hessian_accumulate(dummy, 8, dummy, 4, 8, 8, dummy, 16, None) == lq.LQ_ERR_WORKSPACE
     assert lib.lq_hessian_accumulate(dummy, 8, dummy, 4, 8, 8, ctypes.c_void_p(260), 1 << 30, None) == lq.LQ_ERR_WORKSPACE
+    _bad(lib.lq_hessian_accumulate_host(None, 8, dummy, 4, 8, 8, 2, dummy, 1 << 30, None), "null")
+    assert lib.lq_hessian_accumulate_host(dummy, 8, dummy, 4, 8, 8, 0, dummy, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
+    assert lib.lq_hessian_accumulate_host(dummy, 8, dummy, 4, 8, 4, 2, dummy, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
+    assert lib.lq_hessian_accumulate_host(dummy, 8, dummy, 4, 8, 8, 2, dummy, 16, None) == lq.LQ_ERR_WORKSPACE
+    assert lib.lq_hessian_accumulate_host(dummy, 8, dummy, 0, 8, 8, 2, None, 0, None) == lq.LQ_OK   # no tokens: no-op
     assert lib.lq_cholesky_inv(dummy, 8, 8, ctypes.c_float(-1.0), dummy, 8, dummy, dummy, dummy, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
     assert lib.lq_cholesky_inv(dummy, 8, 8, ctypes.c_float(0.01), dummy, 4, dummy, dummy, dummy, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
     assert lib.lq_cholesky_inv(dummy, 8, 8, ctypes.c_float(0.01), dummy, 8, dummy, dummy, dummy, 8, None) == lq.LQ_ERR_WORKSPACE
@@ -100,3 +105,18 @@ def test_host_side_packing_helpers_match_the_oracle():
     assert lq.lq_packed_row_bytes(-1, 4) == -1 and lq.lq_packed_row_bytes(8, 0) == -1
     bad = lq.lq_params_default(bits=5)
     assert lq.lq_bits_per_weight(3, 4096, bad) == -1.0
+
+
+def test_host_streaming_workspace_is_partial_sums_plus_two_chunk_buffers(lib):
+    """Layout of the scratch of lq_hessian_accumulate_host: the larger partial-sum scratch of
+    the two chunk sizes that occur, then two staging buffers, all 256-byte multiples."""
+    def part(c, n):
+        return lib.lq_workspace_bytes(lq.LQ_CALL_HESSIAN, 0, c, n, None)
+    up = lambda x: (x + 255) // 256 * 256
+    for c, n, ch in [(4096, 262144, 16384), (512, 2048, 512), (300, 1000, 384), (64, 10, 100), (11008, 40000, 8192)]:
+        whole = min(n, ch)
+        tail = n % ch if n > ch else 0
+        p = max(part(c, whole), part(c, tail) if tail else 0)
+        assert lib.lq_hessian_host_workspace_bytes(c, n, ch) == up(p) + 2 * up(whole * c * 4)
+    assert lib.lq_hessian_host_workspace_bytes(0, 10, 10) == 0
+    assert lib.lq_hessian_host_workspace_bytes(8, 10, 0) == 0
