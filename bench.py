@@ -168,6 +168,22 @@ def main():
     torch.cuda.synchronize()
     pack_ms = pe[0].elapsed_time(pe[1]) / 5
 
+    # product of the stored layer with one input vector (decoding-time use of the result):
+    # also apart from `value`; the kernel needs c to be a multiple of 32 and at most 16384
+    matvec_us = None
+    if c % 32 == 0 and c <= 16384 and (P.mode == lq.LQ_GRID_NONUNIFORM or (P.group_size or c) % 32 == 0) \
+            and packed.stride(0) % 16 == 0:
+        xv = torch.randn((1, c), dtype=torch.float32, device="cuda")
+        yv = torch.empty((1, r), dtype=torch.float32, device="cuda")
+        lq.lq_matvec_packed(packed, table, c, P, xv, yv)
+        pe2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        pe2[0].record()
+        for _ in range(20):
+            lq.lq_matvec_packed(packed, table, c, P, xv, yv)
+        pe2[1].record()
+        torch.cuda.synchronize()
+        matvec_us = 1e3 * pe2[0].elapsed_time(pe2[1]) / 20
+
     stage = np.array([[ev[k][i].elapsed_time(ev[k][i + 1]) for i in range(4)] for k in range(args.steps)])
     stage_ms = stage.mean(axis=0)
     # fp32 MFMA Gram product: tiles on or above the diagonal only, 2 flop per multiply-add
@@ -187,7 +203,7 @@ def main():
                                 "quantize_layer": stage_ms[3]},
                    # the same pass when H is reused from a projection with the same input
                    "weights_per_s_without_hessian": r * c / (float(stage_ms[1:].sum()) * 1e-3),
-                   "pack_layer_ms": pack_ms, "bits_per_weight": lq.lq_bits_per_weight(r, c, P)},
+                   "pack_layer_ms": pack_ms, "matvec_packed_us": matvec_us, "bits_per_weight": lq.lq_bits_per_weight(r, c, P)},
         "roofline": {"bound": "mfma", "kernel": "tn_gemm_kernel (H += 2 X^T X, upper tiles) + partial-sum reduce",
                      "achieved": achieved, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / FP32_MFMA_PEAK_TFLOPS,

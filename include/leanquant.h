@@ -162,6 +162,24 @@ lq_status lq_fit_grid_from(const float* W, int64_t r, int64_t c, int64_t ldw, co
                            size_t ws_bytes, void* stream);
 
 /*
+ * Weighted k-means++ seeding of the non-uniform grids: the initialisation that the paper's
+ * appendix table on grid point initialisation compares Eq. 6 against.  Per row, centre 0 is
+ * drawn with probability proportional to omega_i = (hinv_diag_i)^-p (Eq. 5's weights),
+ * centre m with probability proportional to omega_i * min_j (w_i - g_j)^2; a draw takes the
+ * first column whose cumulative mass reaches u * total and, if that column has no mass, the
+ * next one that has; if no mass is left the first column is taken.  All in float64.
+ *   W, r, c, ldw, hinv_diag, P   as lq_fit_grid; P->mode must be LQ_GRID_NONUNIFORM, c <= 16384.
+ *   u          device [r x 2^b] float64 in [0, 1): the uniform numbers of the draws, supplied
+ *              by the caller so that the result is a function of the arguments.
+ *   grid_init  device [r x 2^b] out: the drawn centres (weights of the row) in ascending
+ *              order, ready for lq_fit_grid_from.
+ *   ws         LQ_CALL_FIT_GRID scratch.
+ */
+lq_status lq_kmeanspp_seed(const float* W, int64_t r, int64_t c, int64_t ldw, const float* hinv_diag,
+                           const lq_params* P, const double* u, float* grid_init, void* ws,
+                           size_t ws_bytes, void* stream);
+
+/*
  * Algorithm 1 lines 10-21: for each block of B columns, quantize column by column
  * against the row's grid, scale the error by U_jj, propagate it inside the block,
  * then apply the dense rank-B update to all later columns.

@@ -23,7 +23,7 @@ LQ_CALL_HESSIAN, LQ_CALL_CHOLESKY, LQ_CALL_FIT_GRID, LQ_CALL_QUANTIZE, LQ_CALL_E
 
 EXPORTS = ("lq_params_default", "lq_hessian_accumulate", "lq_hessian_accumulate_host",
            "lq_hessian_host_workspace_bytes", "lq_cholesky_inv", "lq_fit_grid",
-           "lq_fit_grid_from", "lq_quantize_layer", "lq_quantize_exact", "lq_hinv_from_factor", "lq_packed_row_bytes", "lq_bits_per_weight", "lq_pack_layer",
+           "lq_fit_grid_from", "lq_kmeanspp_seed", "lq_quantize_layer", "lq_quantize_exact", "lq_hinv_from_factor", "lq_packed_row_bytes", "lq_bits_per_weight", "lq_pack_layer",
            "lq_unpack_layer", "lq_matvec_packed", "lq_workspace_bytes", "lq_last_error", "lq_version")
 
 
@@ -68,6 +68,8 @@ def load() -> ctypes.CDLL:
     lib.lq_fit_grid.restype = ctypes.c_int
     lib.lq_fit_grid_from.argtypes = [vp, i64, i64, i64, vp, pp, vp, vp, vp, sz, vp]
     lib.lq_fit_grid_from.restype = ctypes.c_int
+    lib.lq_kmeanspp_seed.argtypes = [vp, i64, i64, i64, vp, pp, vp, vp, vp, sz, vp]
+    lib.lq_kmeanspp_seed.restype = ctypes.c_int
     lib.lq_quantize_layer.argtypes = [vp, i64, i64, i64, vp, i64, vp, pp, vp, vp, vp, sz, vp]
     lib.lq_quantize_layer.restype = ctypes.c_int
     lib.lq_quantize_exact.argtypes = [vp, i64, i64, i64, vp, i64, vp, pp, vp, vp, vp, vp, sz, vp]
@@ -202,6 +204,17 @@ def lq_fit_grid_from(W: torch.Tensor, hinv_diag: torch.Tensor, P: lq_params,
                                    _ptr(hinv_diag, torch.float32, "hinv_diag"), ctypes.byref(P),
                                    _ptr(init_grid, torch.float32, "init_grid"),
                                    _ptr(grid, torch.float32, "grid"), wp, wn, _stream()))
+
+
+def lq_kmeanspp_seed(W: torch.Tensor, hinv_diag: torch.Tensor, P: lq_params, u: torch.Tensor,
+                     grid_init: torch.Tensor, ws: torch.Tensor) -> None:
+    """k-means++ seeding of the non-uniform grids; u [r x 2^b] float64 uniforms in [0, 1)."""
+    r, c = W.shape
+    wp, wn = _ws(ws)
+    _check(load().lq_kmeanspp_seed(_ptr(W, torch.float32, "W"), r, c, _ld(W, "W"),
+                                   _ptr(hinv_diag, torch.float32, "hinv_diag"), ctypes.byref(P),
+                                   _ptr(u, torch.float64, "u"), _ptr(grid_init, torch.float32, "grid_init"),
+                                   wp, wn, _stream()))
 
 
 def lq_quantize_layer(W: torch.Tensor, U: torch.Tensor, grid: torch.Tensor, P: lq_params,

@@ -62,6 +62,12 @@ def test_argument_errors_are_host_side(lib):
     assert lib.lq_hessian_accumulate_host(dummy, 8, dummy, 4, 8, 4, 2, dummy, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
     assert lib.lq_hessian_accumulate_host(dummy, 8, dummy, 4, 8, 8, 2, dummy, 16, None) == lq.LQ_ERR_WORKSPACE
     assert lib.lq_hessian_accumulate_host(dummy, 8, dummy, 0, 8, 8, 2, None, 0, None) == lq.LQ_OK   # no tokens: no-op
+    _bad(lib.lq_kmeanspp_seed(dummy, 4, 8, 8, dummy, pp, None, dummy, dummy, 1 << 30, None), "null")
+    assert lib.lq_kmeanspp_seed(dummy, 4, 8, 4, dummy, pp, dummy, dummy, dummy, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
+    assert lib.lq_kmeanspp_seed(dummy, 4, 8, 8, dummy, pp, dummy, dummy, dummy, 8, None) == lq.LQ_ERR_WORKSPACE
+    assert lib.lq_kmeanspp_seed(dummy, 4, 32768, 32768, dummy, pp, dummy, dummy, dummy, 1 << 30, None) == lq.LQ_ERR_UNSUPPORTED
+    Paff = lq.lq_params_default(bits=4, mode=lq.LQ_GRID_AFFINE, group_size=8)
+    assert lib.lq_kmeanspp_seed(dummy, 4, 8, 8, dummy, ctypes.byref(Paff), dummy, dummy, dummy, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
     assert lib.lq_cholesky_inv(dummy, 8, 8, ctypes.c_float(-1.0), dummy, 8, dummy, dummy, dummy, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
     assert lib.lq_cholesky_inv(dummy, 8, 8, ctypes.c_float(0.01), dummy, 4, dummy, dummy, dummy, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
     assert lib.lq_cholesky_inv(dummy, 8, 8, ctypes.c_float(0.01), dummy, 8, dummy, dummy, dummy, 8, None) == lq.LQ_ERR_WORKSPACE

@@ -70,3 +70,61 @@ def test_starting_grid_is_rejected_for_affine_grids():
     P = lq.lq_params_default(bits=4, mode=lq.LQ_GRID_AFFINE, group_size=64)
     with pytest.raises(lq.LeanQuantError):
         hx.gpu_fit_grid(hx.to_dev(W), hx.to_dev(d), P, init=torch.zeros((4, 16), device="cuda"))
+
+
+def _gpu_seed(lq, W, d, P, u):
+    r, c = W.shape
+    out = torch.empty((r, 1 << P.bits), dtype=torch.float32, device="cuda")
+    ws = lq.alloc_workspace(lq.lq_workspace_bytes(lq.LQ_CALL_FIT_GRID, r, c, 0, P))
+    lq.lq_kmeanspp_seed(hx.to_dev(W), hx.to_dev(d), P, hx.to_dev(u, torch.float64), out, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+@pytest.mark.parametrize("bits,r,c,p", [(2, 64, 512, 4.0), (3, 96, 768, 4.0), (4, 48, 2048, 4.0),
+                                         (4, 7, 5000, 2.0), (3, 5, 16384, 4.0), (4, 5, 10, 4.0),
+                                         (2, 3, 1, 4.0), (4, 33, 300, 0.0)])
+def test_kmeanspp_seeding_on_the_gpu_draws_the_oracles_centres(bits, r, c, p):
+    """The draws are decided in float64 on both sides from the same uniform numbers: the
+    drawn centres (weights of the row) are identical."""
+    lq = _lq()
+    print(f"k-means++ seeding bits={bits} r={r} c={c} p={p}", flush=True)
+    W, d = _case(r, c, 700 + bits + c)
+    u = np.random.default_rng(710 + bits + c).random((r, 1 << bits))
+    u[0, 0] = 0.0                                        # the first column with mass
+    P = lq.lq_params_default(bits=bits, p=p)
+    got = _gpu_seed(lq, W, d, P, u)
+    ref = orc.kmeanspp_init(W, d, bits, p, u).astype(np.float32)
+    assert np.array_equal(got, ref)
+
+
+def test_kmeanspp_seeding_degenerate_rows():
+    """A constant row has no mass left after its first centre (every draw then takes column
+    0); a row with a few distinct values runs out of mass once each has been drawn."""
+    lq = _lq()
+    c = 200
+    W = np.zeros((3, c), dtype=np.float32)
+    W[0, :] = 0.125
+    W[1, :] = np.where(np.arange(c) % 3 == 0, -0.5, 0.25)
+    W[2, :] = np.linspace(-1, 1, c)
+    d = np.exp(np.random.default_rng(3).standard_normal(c)).astype(np.float32)
+    u = np.random.default_rng(4).random((3, 16))
+    P = lq.lq_params_default(bits=4)
+    got = _gpu_seed(lq, W, d, P, u)
+    ref = orc.kmeanspp_init(W, d, 4, 4.0, u).astype(np.float32)
+    assert np.array_equal(got, ref)
+    assert np.all(got[0] == 0.125)
+    assert set(np.unique(got[1])) == {np.float32(-0.5), np.float32(0.25)}
+
+
+def test_lloyd_from_gpu_seeding_end_to_end():
+    """Seeding and Lloyd iteration both on the GPU against both in the oracle."""
+    lq = _lq()
+    bits, r, c = 3, 64, 1024
+    W, d = _case(r, c, 801)
+    u = np.random.default_rng(802).random((r, 1 << bits))
+    P = lq.lq_params_default(bits=bits)
+    init = _gpu_seed(lq, W, d, P, u)
+    G = hx.gpu_fit_grid(hx.to_dev(W), hx.to_dev(d), P, init=hx.to_dev(init)).cpu().numpy()
+    ref_init = orc.kmeanspp_init(W, d, bits, 4.0, u)
+    _accept(W, d, 4.0, G, orc.fit_grid_nu(W, d, bits, 4.0, init=ref_init))
