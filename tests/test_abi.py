@@ -126,3 +126,40 @@ def test_host_streaming_workspace_is_partial_sums_plus_two_chunk_buffers(lib):
         assert lib.lq_hessian_host_workspace_bytes(c, n, ch) == up(p) + 2 * up(whole * c * 4)
     assert lib.lq_hessian_host_workspace_bytes(0, 10, 10) == 0
     assert lib.lq_hessian_host_workspace_bytes(8, 10, 0) == 0
+
+
+def test_argument_errors_of_the_calls_beyond_the_pass(lib):
+    """Stored form, product, Algorithm 2: every bad argument is refused on the host."""
+    P = lq.lq_params_default()
+    pp = ctypes.byref(P)
+    d = ctypes.c_void_p(256)
+    # lq_pack_layer(codes, grid, r, c, P, packed, packed_ld, table, stream)
+    assert lib.lq_pack_layer(d, d, 0, 64, pp, d, 32, d, None) == lq.LQ_OK           # no rows
+    _bad(lib.lq_pack_layer(None, d, 4, 64, pp, d, 32, d, None), "null")
+    assert lib.lq_pack_layer(d, d, 4, 64, pp, d, 31, d, None) == lq.LQ_ERR_INVALID_ARG
+    # lq_unpack_layer(packed, packed_ld, table, r, c, P, W_hat, ldw, codes, stream)
+    assert lib.lq_unpack_layer(d, 32, d, 0, 64, pp, d, 64, None, None) == lq.LQ_OK
+    _bad(lib.lq_unpack_layer(d, 32, None, 4, 64, pp, d, 64, None, None), "null")
+    assert lib.lq_unpack_layer(d, 32, d, 4, 64, pp, d, 63, None, None) == lq.LQ_ERR_INVALID_ARG
+    # lq_matvec_packed(packed, packed_ld, table, r, c, P, X, nb, Y, stream)
+    assert lib.lq_matvec_packed(d, 32, d, 0, 64, pp, d, 1, d, None) == lq.LQ_OK
+    assert lib.lq_matvec_packed(d, 32, d, 4, 64, pp, d, 0, d, None) == lq.LQ_OK
+    _bad(lib.lq_matvec_packed(d, 32, d, 4, 64, pp, None, 1, d, None), "null")
+    assert lib.lq_matvec_packed(d, 16, d, 4, 64, pp, d, 1, d, None) == lq.LQ_ERR_INVALID_ARG     # ld < row bytes
+    assert lib.lq_matvec_packed(d, 48, d, 4, 72, pp, d, 1, d, None) == lq.LQ_ERR_UNSUPPORTED     # c % 32
+    assert lib.lq_matvec_packed(d, 16384, d, 4, 32768, pp, d, 1, d, None) == lq.LQ_ERR_UNSUPPORTED
+    assert lib.lq_matvec_packed(d, 40, d, 4, 64, pp, d, 1, d, None) == lq.LQ_ERR_UNSUPPORTED     # rows not 16-byte aligned
+    assert lib.lq_matvec_packed(ctypes.c_void_p(260), 32, d, 4, 64, pp, d, 1, d, None) == lq.LQ_ERR_UNSUPPORTED
+    Pa = lq.lq_params_default(bits=4, mode=lq.LQ_GRID_AFFINE, group_size=16)
+    assert lib.lq_matvec_packed(d, 32, d, 4, 64, ctypes.byref(Pa), d, 1, d, None) == lq.LQ_ERR_UNSUPPORTED
+    # lq_quantize_exact(W, r, c, ldw, Hinv, ldh, grid, P, codes, row_loss, order, ws, ws_bytes, stream)
+    assert lib.lq_quantize_exact(d, 0, 8, 8, d, 8, d, pp, d, None, None, d, 1 << 30, None) == lq.LQ_OK
+    _bad(lib.lq_quantize_exact(d, 4, 8, 8, None, 8, d, pp, d, None, None, d, 1 << 30, None), "null")
+    assert lib.lq_quantize_exact(d, 4, 8, 4, d, 8, d, pp, d, None, None, d, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
+    assert lib.lq_quantize_exact(d, 4, 4096, 4096, d, 4096, d, pp, d, None, None, d, 1 << 30, None) == lq.LQ_ERR_UNSUPPORTED
+    assert lib.lq_quantize_exact(d, 4, 8, 8, d, 8, d, pp, d, None, None, d, 8, None) == lq.LQ_ERR_WORKSPACE
+    Pg = lq.lq_params_default(bits=4, mode=lq.LQ_GRID_AFFINE, group_size=4)
+    assert lib.lq_quantize_exact(d, 4, 8, 8, d, 8, d, ctypes.byref(Pg), d, None, None, d, 1 << 30, None) == lq.LQ_ERR_INVALID_ARG
+    # lq_hinv_from_factor(U, ldu, c, Hinv, ldh, stream)
+    _bad(lib.lq_hinv_from_factor(None, 8, 8, d, 8, None), "null")
+    assert lib.lq_hinv_from_factor(d, 4, 8, d, 8, None) == lq.LQ_ERR_INVALID_ARG
