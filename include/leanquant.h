@@ -258,7 +258,8 @@ lq_status lq_unpack_layer(const uint8_t* packed, int64_t packed_ld, const uint16
  *   packed, table  as written by lq_pack_layer for the same P; packed rows 16 / 4 / 8-byte
  *                  aligned for 4 / 3 / 2 bits (base pointer and packed_ld).
  *   X  [nb x c] fp32, rows contiguous, 16-byte aligned;  Y [nb x r] fp32 out.
- * The codes are read once per input vector (nb passes).  Limits: c a multiple of 32 and at
+ * One pass over the codes serves up to 4 input vectors (2 for c > 8192); larger nb takes
+ * ceil(nb / 4) passes.  Limits: c a multiple of 32 and at
  * most 16384; affine groups multiples of 32 columns.  No workspace.
  */
 lq_status lq_matvec_packed(const uint8_t* packed, int64_t packed_ld, const uint16_t* table, int64_t r,

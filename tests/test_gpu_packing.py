@@ -137,7 +137,8 @@ def test_projections_sharing_an_input_are_quantized_in_one_pass():
 
 @pytest.mark.parametrize("mode,bits,group", [("nu", 4, 0), ("nu", 3, 0), ("nu", 2, 0),
                                              ("aff", 4, 128), ("aff", 2, 64), ("aff", 3, 0)])
-@pytest.mark.parametrize("r,c,nb", [(5, 32, 1), (37, 1024, 3), (100, 4096, 1), (19, 11008, 2), (16, 16384, 1)])
+@pytest.mark.parametrize("r,c,nb", [(5, 32, 1), (37, 1024, 3), (100, 4096, 1), (19, 11008, 2), (16, 16384, 1),
+                                    (64, 2048, 7), (40, 11008, 5)])
 def test_matvec_from_the_stored_form(mode, bits, group, r, c, nb):
     lq = _lq()
     if mode == "aff" and group and c % group:
