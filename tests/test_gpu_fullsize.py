@@ -1,5 +1,5 @@
-"""The largest benchmark layer (configuration 5, non-uniform 3-bit) at its FULL size:
-53248 x 16384 weights, 65536 calibration tokens accumulated in chunks of 8192.
+"""The large benchmark layers (configurations 3, 4 and 5, the latter with both grid kinds) at
+their FULL sizes, calibration tokens accumulated in chunks.
 
 The float64 oracle cannot run this end to end in minutes, so the checks are
   * properties that hold at any size, over every row: W_hat is exactly grid[row][code],
@@ -31,18 +31,21 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def test_config5_non_uniform_full_size():
-    cfg = lq_synth.CONFIGS["c5nu"]
+@pytest.mark.parametrize("name", ["c5nu", "c3"])
+def test_non_uniform_configurations_at_full_size(name):
+    """c5nu: 53248 x 16384 weights, 65536 tokens, 3 bits; c3: 4096 x 11008 weights, 262144
+    tokens of the gated-activation kind, 3 bits."""
+    cfg = lq_synth.CONFIGS[name]
     P = hx.params_for(cfg)
     r, c, n = cfg.r, cfg.c, cfg.n_tokens
     t0 = time.time()
-    _say(f"c5nu full size: W {r} x {c}, X {n} x {c}")
+    _say(f"{name} full size: W {r} x {c}, X {n} x {c}")
 
     # ---- stage A in chunks; oracle Gram on sampled tiles
     H = torch.zeros((c, c), dtype=torch.float32, device="cuda")
     ws = lq.alloc_workspace(lq.lq_workspace_bytes(lq.LQ_CALL_HESSIAN, 0, c, lq_synth.TOKEN_CHUNK))
     rng = np.random.default_rng(5150)
-    tiles = [(int(a), int(b)) for a, b in rng.integers(0, c // 128, size=(6, 2))] + [(3, 3), (127, 127)]
+    tiles = [(int(a), int(b)) for a, b in rng.integers(0, c // 128, size=(6, 2))] + [(3, 3), (c // 128 - 1, c // 128 - 1)]
     ref_tiles = [np.zeros((128, 128)) for _ in tiles]
     for k in range(lq_synth.n_token_chunks(cfg)):
         xc = lq_synth.activation_chunk(cfg, k)
@@ -182,3 +185,66 @@ def test_config4_affine_full_size():
         assert agree >= 0.999
         rl = row_loss[rows].cpu().numpy()[row_ok]
         assert np.max(np.abs(rl - loss_ref) / loss_ref) < 1e-3
+
+
+def test_config5_affine_full_size():
+    """Configuration 5 with 2-bit affine grids of 64 columns (13.6 M groups, t = 0.4 T) at its
+    full size.  The oracle's enumeration takes a quarter of a second per group, so stage C is
+    checked on sampled groups and stage D on sampled rows from the device's own grids (rows
+    and groups are independent problems)."""
+    cfg = lq_synth.CONFIGS["c5"]
+    P = hx.params_for(cfg)
+    r, c, n = cfg.r, cfg.c, cfg.n_tokens
+    g = cfg.group_size
+    qmax = float((1 << cfg.bits) - 1)
+    t0 = time.time()
+    _say(f"c5 affine full size: W {r} x {c}, X {n} x {c}, groups of {g}")
+    H = torch.zeros((c, c), dtype=torch.float32, device="cuda")
+    ws = lq.alloc_workspace(lq.lq_workspace_bytes(lq.LQ_CALL_HESSIAN, 0, c, lq_synth.TOKEN_CHUNK))
+    for k in range(lq_synth.n_token_chunks(cfg)):
+        lq.lq_hessian_accumulate(H, torch.from_numpy(lq_synth.activation_chunk(cfg, k)).cuda(), ws)
+    U, d, info = hx.gpu_cholesky(H, P.damp)
+    assert info == 0
+    del H
+    _say(f"  H, U, d done ({time.time() - t0:.0f} s)")
+    W = torch.from_numpy(lq_synth.weights(cfg)).cuda()
+    SZ = hx.gpu_fit_grid(W, d, P)
+    What, codes, row_loss = hx.gpu_quantize(W, U, SZ, P)
+    _say(f"  fit + loop on all rows done ({time.time() - t0:.0f} s)")
+    assert bool(torch.all(SZ[..., 0] > 0)) and bool(torch.all(SZ[..., 1] == torch.round(SZ[..., 1])))
+    assert bool(torch.all(codes <= int(qmax)))
+    for s0 in range(0, r, 8192):                        # W_hat = (code - Z) S, in row slabs
+        sl = slice(s0, min(r, s0 + 8192))
+        S = SZ[sl, :, 0].repeat_interleave(g, dim=1)
+        Z = SZ[sl, :, 1].repeat_interleave(g, dim=1)
+        assert torch.equal(What[sl], (codes[sl].float() - Z) * S)
+    assert bool(torch.all(torch.isfinite(row_loss))) and bool(torch.all(row_loss >= 0))
+    # stage C: sampled groups against the enumeration
+    rng = np.random.default_rng(5252)
+    dcpu = d.cpu().numpy()
+    om = orc.importance(dcpu, cfg.p)
+    t_lim = orc.shrink_steps(cfg.bits, cfg.T)
+    same = 0
+    picks = [(int(rng.integers(r)), int(rng.integers(c // g))) for _ in range(16)]
+    for k, gi in picks:
+        sl = slice(gi * g, (gi + 1) * g)
+        w = W[k, sl].cpu().numpy()
+        S_ref, Z_ref, loss_ref, _, _ = orc.fit_group_aff(w, om[sl], cfg.bits, cfg.T, t_lim)
+        S_g, Z_g = float(SZ[k, gi, 0]), float(SZ[k, gi, 1])
+        if abs(S_g - S_ref) <= 1e-4 * abs(S_ref) and Z_g == Z_ref:
+            same += 1
+        else:
+            got = orc.eq7_objective(w, om[sl], S_g, Z_g, cfg.bits)
+            assert got <= loss_ref * (1 + 1e-5), (k, gi, got, loss_ref)
+    _say(f"  sampled groups identical: {same} of {len(picks)} ({time.time() - t0:.0f} s)")
+    assert same >= len(picks) - 1
+    # stage D: sampled rows, the oracle's column loop from the device's grids and U
+    rows = np.sort(rng.choice(r, size=4, replace=False))
+    U64 = U.cpu().numpy().astype(np.float64)
+    _, codes_ref, loss_ref = orc.quantize_layer(W[rows].cpu().numpy(), U64, SZ[rows].cpu().numpy().astype(np.float64),
+                                                "aff", cfg.bits, group_size=g, B=cfg.block)
+    agree = hx.code_agreement(codes[rows].cpu().numpy(), codes_ref)
+    _say(f"  codes equal on sampled rows: {agree:.5f} ({time.time() - t0:.0f} s)")
+    assert agree >= 0.999
+    rl = row_loss[rows].cpu().numpy()
+    assert np.max(np.abs(rl - loss_ref) / loss_ref) < 1e-3
