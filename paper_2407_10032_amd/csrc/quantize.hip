@@ -19,9 +19,14 @@
 #include "lq_quantize_col.h"
 
 namespace {
+#ifndef LQ_GROUP8_ROWS
+#define LQ_GROUP8_ROWS 16384
+#endif
 
 constexpr int KT = 32;
-constexpr int GROUP = 4;   // blocks whose far-field updates are applied together
+// blocks whose far-field updates are applied together: more for layers with many rows, where
+// the far field is large and each pass over it costs its read-modify-write traffic
+inline int group_blocks(int64_t r) { return r >= LQ_GROUP8_ROWS ? 8 : 4; }
 
 // Pack the diagonal B x B blocks of U: ud[blk][j][jj] = U[i0+j][i0+jj] for jj >= j inside the
 // matrix, zero elsewhere; urinv[blk][j] = 1 / U[i0+j][i0+j] (0 outside the matrix).
@@ -49,7 +54,7 @@ QuantPlan make_plan(int64_t r, int64_t c, int B) {
   QuantPlan p;
   p.rpad = lq::ceil_div(r > 0 ? r : 1, lq::QT) * lq::QT;   // one slot per lane of the column kernel
   p.nblk = lq::ceil_div(c, B);
-  p.off_ud = lq::align_up((size_t)p.rpad * B * GROUP * sizeof(float), 256);
+  p.off_ud = lq::align_up((size_t)p.rpad * B * group_blocks(r) * sizeof(float), 256);
   p.off_rinv = p.off_ud + lq::align_up((size_t)p.nblk * B * B * sizeof(float), 256);
   p.total = p.off_rinv + lq::align_up((size_t)p.nblk * B * sizeof(float), 256);
   return p;
@@ -147,6 +152,7 @@ extern "C" lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t l
   };
 
   float* const et_base = a.Et;
+  const int GROUP = group_blocks(r);
   for (int64_t i0 = 0; i0 < c; i0 += B) {
     const int64_t blk = i0 / B;
     const int64_t li = blk % GROUP;                       // position inside the group
