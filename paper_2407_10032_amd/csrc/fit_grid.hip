@@ -115,16 +115,20 @@ __global__ __launch_bounds__(NT) void kmeans_rows_kernel(const float* __restrict
       float* mine = sAcc + tid * ACC_LD;
 #pragma unroll
       for (int m = 0; m < 2 * K; ++m) mine[m] = 0.0f;
+      // Columns past c hold w = 0 with omega = 0 and add nothing.  The cluster of a weight is
+      // the number of midpoints below it, counted from the sign bits of mid - w (w > mid
+      // exactly when the difference is negative): no comparison masks, no selects, no
+      // branches, so the loop is one block and the LDS updates of one weight overlap the
+      // counting of the next.  (Measured alternatives: a bisection over the midpoints, same
+      // speed; the read-add-writes of four weights batched, 8 % slower; LDS float atomics on
+      // the thread's own slots, five times slower.)
 #pragma unroll
       for (int e = 0; e < EPT; ++e) {
-        int64_t col = (int64_t)e * NT + tid;
-        if (col < c) {
-          int idx = 0;
+        uint32_t cnt = 0;
 #pragma unroll
-          for (int m = 0; m < K - 1; ++m) idx += (w[e] > mid[m]) ? 1 : 0;
-          mine[idx] += om[e] * w[e];
-          mine[K + idx] += om[e];
-        }
+        for (int m = 0; m < K - 1; ++m) cnt += __float_as_uint(mid[m] - w[e]) >> 31;
+        mine[cnt] += om[e] * w[e];
+        mine[K + cnt] += om[e];
       }
       __syncthreads();
       {
