@@ -4,7 +4,8 @@
 
 For one seeded synthetic layer: H, U and d are computed once (Algorithm 1 lines 3-4); then,
 for every bit width, the outlier-preservation strength p of Eq. 5 in {0, 2, 3, 4} and the
-two initialisations (Eq. 6 and k-means++), the grids are learned and the column loop run, and
+two initialisations (Eq. 6 and k-means++), and for affine grids the search of Eq. 7 against
+the plain min-max grid, the grids are learned and the column loop run, and
 the layer's loss  sum_k 1/2 (w_k - w_hat_k) H_d (w_k - w_hat_k)^T  (the sum the loop's scaled
 errors add up to) is printed relative to the p = 4 / Eq. 6 setting of the paper.  Everything
 runs on the GPU through the C ABI; the uniform numbers of the k-means++ draws come from a
@@ -31,9 +32,15 @@ def layer_loss(W, U, d, P, init):
     """init: None (Eq. 6) or a device tensor [r x 2^b] of uniforms for k-means++ seeding."""
     r, c = W.shape
     K = 1 << P.bits
-    grid = torch.empty((r, K), dtype=torch.float32, device="cuda")
     ws = _ws(lq.LQ_CALL_FIT_GRID, r, c, 0, P)
-    if init is None:
+    if P.mode == lq.LQ_GRID_AFFINE:
+        g = P.group_size if P.group_size > 0 else c
+        grid = torch.empty((r, c // g, 2), dtype=torch.float32, device="cuda")
+    else:
+        grid = torch.empty((r, K), dtype=torch.float32, device="cuda")
+    if P.mode == lq.LQ_GRID_AFFINE:
+        lq.lq_fit_grid(W, d, P, grid, ws)
+    elif init is None:
         lq.lq_fit_grid(W, d, P, grid, ws)
     else:
         seed = torch.empty((r, K), dtype=torch.float32, device="cuda")
@@ -92,6 +99,20 @@ def main():
                 rows.append((bits, p, name, loss, loss / base))
         for b, p, name, loss, rel in rows:
             print("%-5d %-6g %-10s %14.6e %10.4f" % (b, p, name, loss, rel))
+    # affine grids: the search of Eq. 7 against the plain min-max grid (no shrinking, t = 0,
+    # the grid of the GPTQ baseline), with and without the loss-error-aware weights
+    print("%-5s %-6s %-6s %-10s %14s %10s" % ("bits", "group", "p", "grid", "sum of loss", "vs paper"))
+    for bits, group in ((4, 128), (3, 128), (2, 64)):
+        if c % group:
+            continue
+        base = None
+        for p, t_override, name in ((4.0, -1, "Eq. 7"), (0.0, -1, "Eq. 7"), (4.0, 0, "min-max")):
+            P = lq.lq_params_default(bits=bits, mode=lq.LQ_GRID_AFFINE, group_size=group, block=cfg.block,
+                                     damp=cfg.damp, p=p, T=cfg.T, t_override=t_override)
+            loss = layer_loss(W, U, d, P, None)
+            if base is None:
+                base = loss
+            print("%-5d %-6d %-6g %-10s %14.6e %10.4f" % (bits, group, p, name, loss, loss / base))
 
 
 if __name__ == "__main__":
