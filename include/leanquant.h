@@ -10,6 +10,12 @@
  *                                         (Eq. 5 with Eq. 6 init, or Eq. 7 with Eq. 8)
  *   lq_quantize_layer       lines 10-21   blocked quantize-and-propagate column loop
  *
+ * Around them: lq_hessian_accumulate_host (line 3 with X streamed from host memory),
+ * lq_fit_grid_from / lq_kmeanspp_seed (Lloyd iteration from another start, the k-means++
+ * seeding of the paper's initialisation table), lq_quantize_exact / lq_hinv_from_factor
+ * (Algorithm 2, LeanQuant-Exact), lq_pack_layer / lq_unpack_layer / lq_matvec_packed (the
+ * stored form behind the "Bits" columns of the result tables and the product with it).
+ *
  * Conventions shared by all calls
  *   - Every pointer is a DEVICE pointer unless the comment says "host".  The
  *     caller owns every buffer; the library allocates no device memory and
@@ -21,10 +27,11 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; they do not synchronize.  Results are
  *     bit-identical from run to run (no atomics on floating-point data).
- *     lq_cholesky_inv also runs part of its work on an internal side stream
- *     (created once per host thread and device, default priority), forked from
- *     and joined back into `stream` with events, so ordering with respect to
- *     `stream` is unchanged.
+ *     lq_cholesky_inv and lq_hessian_accumulate_host also run part of their work on
+ *     internal side streams (created once per host thread and device, default
+ *     priority), forked from and joined back into `stream` with events, so ordering
+ *     with respect to `stream` is unchanged.  The calls of the pass can be recorded
+ *     into a HIP graph (kernels and event waits only).
  *   - `ws` is caller-provided scratch of at least lq_workspace_bytes() bytes,
  *     256-byte aligned, whose contents are undefined before and after a call.
  *   - Return value: LQ_OK or an error code; argument errors are found on the
