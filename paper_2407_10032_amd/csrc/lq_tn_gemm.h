@@ -387,27 +387,41 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void tn_gemm_kernel(TnGemmArgs a)
     // thread reads, updates and writes whole 16-byte pieces of C rows, with all of its
     // sixteen loads in flight before the first add (element-wise read-modify-write from
     // the accumulator layout is serialized by the possible aliasing of its own stores).
-    __syncthreads();                               // every wave is done reading the last stage
-#pragma unroll
-    for (int tm = 0; tm < 2; ++tm)
-#pragma unroll
-      for (int tn = 0; tn < 2; ++tn)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          smem[acc_row(wm, tm, v, lane) * TILE + acc_col(wn, tn, lane)] = a.alpha * acc.t[tm][tn][v];
-    __syncthreads();
+    // The staging area is the operand buffers: a whole tile at once where they hold 64 KB
+    // (32-row stages), otherwise the two 64-row halves one after the other (the rows of
+    // half h are the sub-tiles tm = h of every wavefront).
     float* cbase = a.C + m0 * a.ldc + n0;
     float4 cv[16];
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
-      const int f = tid + u * WG_THREADS;
+      const int f = tid + u * WG_THREADS;            // u < 8: rows 0..63, u >= 8: rows 64..127
       cv[u] = *reinterpret_cast<const float4*>(cbase + (int64_t)(f >> 5) * a.ldc + 4 * (f & 31));
     }
+    constexpr int HALVES = (4 * KT * TILE >= TILE * TILE) ? 1 : 2;
+    static_assert(4 * KT * TILE * HALVES >= TILE * TILE, "staging area");
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int f = tid + u * WG_THREADS;
-      const float4 d = *reinterpret_cast<const float4*>(smem + (f >> 5) * TILE + 4 * (f & 31));
-      cv[u].x += d.x; cv[u].y += d.y; cv[u].z += d.z; cv[u].w += d.w;
+    for (int h = 0; h < HALVES; ++h) {
+      __syncthreads();                             // the buffers (or the previous half) are no longer read
+#pragma unroll
+      for (int tm = 0; tm < 2; ++tm) {
+        if (HALVES == 2 && tm != h) continue;
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = acc_row(wm, tm, v, lane) - (HALVES == 2 ? 64 * h : 0);
+            smem[row * TILE + acc_col(wn, tn, lane)] = a.alpha * acc.t[tm][tn][v];
+          }
+      }
+      __syncthreads();
+      constexpr int PER = 16 / HALVES;
+#pragma unroll
+      for (int u2 = 0; u2 < PER; ++u2) {
+        const int u = h * PER + u2;
+        const int f = tid + u2 * WG_THREADS;         // position inside the staged rows
+        const float4 d = *reinterpret_cast<const float4*>(smem + (f >> 5) * TILE + 4 * (f & 31));
+        cv[u].x += d.x; cv[u].y += d.y; cv[u].z += d.z; cv[u].w += d.w;
+      }
     }
 #pragma unroll
     for (int u = 0; u < 16; ++u) {

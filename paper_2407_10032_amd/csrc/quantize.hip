@@ -23,7 +23,8 @@ namespace {
 #define LQ_GROUP8_ROWS 16384
 #endif
 
-constexpr int KT = 32;
+constexpr int KT = 16;      // rows of E^T and U per stage of the trailing product
+constexpr int MINW = 3;    // resident workgroups per CU the kernel is compiled for
 // blocks whose far-field updates are applied together: more for layers with many rows, where
 // the far field is large and each pass over it costs its read-modify-write traffic
 inline int group_blocks(int64_t r) { return r >= LQ_GROUP8_ROWS ? 8 : 4; }
@@ -105,9 +106,9 @@ extern "C" lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t l
   const size_t gemm_lds = 4 * KT * lq::TILE * sizeof(float);
   static bool attr_done = false;
   if (!attr_done) {
-    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, false, false, true>,
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, false, false, true, MINW>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds));
-    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, false, false, false>,
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, false, false, false, MINW>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds));
     attr_done = true;
   }
@@ -144,9 +145,9 @@ extern "C" lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t l
     }
     dim3 grid2((unsigned)t.ntiles);
     if (vec)
-      hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, false, false, true>), grid2, block2, gemm_lds, st, t);
+      hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, false, false, true, MINW>), grid2, block2, gemm_lds, st, t);
     else
-      hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, false, false, false>), grid2, block2, gemm_lds, st, t);
+      hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, false, false, false, MINW>), grid2, block2, gemm_lds, st, t);
     LQ_CHECK_LAUNCH("tn_gemm_kernel(trailing)");
     return LQ_OK;
   };
