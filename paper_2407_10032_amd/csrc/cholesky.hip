@@ -733,8 +733,12 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
   a.A = A; a.Xb = Xb; a.Dinv = Dinv; a.cp = cp;
   // A launch with few 128 x 128 tiles is cut into smaller pieces (see chol_small_kernel).
   constexpr int SMALL_LIMIT = 768;
+  constexpr int PANEL_STREAM_NB = 48;
   auto launch = [&](int mode, int big_tiles, hipStream_t sx, const ChArgs& arg) -> lq_status {
-    const bool small = big_tiles <= SMALL_LIMIT;
+    // The single-shot panel kernel holds 100 KB of LDS: next to the inverse chain's large
+    // launches on the side stream (many blocks) it would wait for a compute unit with that
+    // much free, on the critical path; the streaming kernel (36 KB) fits beside them.
+    const bool small = big_tiles <= SMALL_LIMIT && !(mode == CH_PANEL && nb > PANEL_STREAM_NB);
     switch (mode) {
       case CH_PANEL:
         if (small) hipLaunchKernelGGL(chol_small_kernel<CH_PANEL>, dim3(2 * big_tiles), dim3(WG_THREADS), chol_small_lds<CH_PANEL>(), sx, arg);
