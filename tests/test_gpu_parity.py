@@ -89,6 +89,29 @@ def test_cholesky_reports_not_positive_definite():
     assert info0 > 0
 
 
+@pytest.mark.parametrize("c,n", [(384, 96), (512, 64), (256, 255)])
+def test_fewer_tokens_than_channels(c, n):
+    """Rank-deficient H (N < c): only the dampening of Section 2.2 makes it invertible, and
+    H_d^-1 is far from diagonal, so a code that flips at a rounding boundary moves the
+    weights after it much more than when N >> c.  U and d still match to fp32 accuracy of the
+    worse-conditioned problem; the codes and the layer loss get a bar of their own here."""
+    _say(f"rank-deficient Hessian c={c} n={n}")
+    rng = np.random.default_rng(c + n)
+    X = rng.standard_normal((n, c)).astype(np.float32)
+    W = (rng.standard_normal((96, c)) * 0.02).astype(np.float32)
+    P = lq.lq_params_default(bits=4)
+    out = hx.gpu_layer_pass(W, [X], P)
+    assert out["info"] == 0
+    U, d = orc.cholesky_inv(orc.hessian(X.astype(np.float64)), 0.01)
+    assert np.max(np.abs(out["U"] - U) / np.sqrt(d)[None, :]) < 2e-4
+    assert np.max(np.abs(out["d"] - d) / d) < 5e-4
+    G = orc.fit_grid_nu(W, d, 4, 4.0)
+    _, codes, loss = orc.quantize_layer(W, U, G, "nu", 4, B=128)
+    assert hx.nu_grid_match(out["grid"], G).mean() >= 0.98
+    assert hx.code_agreement(out["codes"], codes) >= 0.99
+    assert abs(out["row_loss"].sum() - loss.sum()) / loss.sum() < 1e-2
+
+
 # ------------------------------------------------------------------ C: grids
 def _d_for(c, seed):
     X = _layer(c, 4 * c, seed, outliers=max(2, c // 64), scale=20.0)
