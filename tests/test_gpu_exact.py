@@ -69,6 +69,31 @@ def test_exact_stage_isolated_matches_oracle(mode, bits, r, c):
         assert abs(loss[k] - eps) <= 1e-5 * eps
 
 
+def test_exact_on_a_wide_layer():
+    """c = 1024, 256 rows (one workgroup each, sharing the memory bandwidth): the energy
+    identity on every row, and one row against the oracle (O(c^3) on the host)."""
+    lq = _lq()
+    r, c = 256, 1024
+    print(f"exact r={r} c={c}", flush=True)
+    W, X = _case(r, c, 3 * c, 4242)
+    Hd = orc.dampen(orc.hessian(X), 0.01)
+    Hinv = np.linalg.inv(Hd)
+    Hinv = 0.5 * (Hinv + Hinv.T)
+    grid = orc.fit_grid_nu(W, np.diag(Hinv).copy(), 4, 4.0).astype(np.float32)
+    P = lq.lq_params_default(bits=4)
+    What, codes, order, loss = _run_exact(lq, W, torch.from_numpy(Hinv).cuda(), grid, P)
+    assert np.array_equal(np.sort(order, axis=1), np.tile(np.arange(c), (r, 1)))   # every column once
+    assert np.array_equal(What, np.take_along_axis(grid, codes.astype(np.int64), axis=1))
+    delta = W.astype(np.float64) - What.astype(np.float64)
+    energy = 0.5 * np.einsum("kj,kj->k", delta @ Hd, delta)     # sum of Eq. 3's loss errors per row
+    assert np.max(np.abs(loss - energy) / energy) < 1e-5
+    k = 77
+    wh, cd, od, eps = orc.exact_row(W[k], Hinv, lambda v: orc.quant_nu(v, grid[k].astype(np.float64)))
+    assert np.array_equal(order[k], od)
+    assert np.array_equal(codes[k], cd)
+    assert np.array_equal(What[k], wh.astype(np.float32))
+
+
 def test_exact_end_to_end_from_the_device_factor():
     lq = _lq()
     r, c = 48, 256
