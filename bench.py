@@ -106,7 +106,6 @@ def main():
 
     import lq_synth
     import paper_2407_10032_amd as lq
-    from tests import lq_harness as hx
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
@@ -114,7 +113,7 @@ def main():
     cfg = lq_synth.CONFIGS[args.config]
     if args.tokens:
         cfg = cfg.scaled(n_tokens=args.tokens)
-    P = hx.params_for(cfg)
+    P = lq.params_for(cfg)
     r, c, n = cfg.r, cfg.c, cfg.n_tokens
     log("generating %s: W %d x %d, X %d x %d" % (cfg.name, r, c, n, c))
     X, W = load_inputs(cfg, torch, lq_synth)
@@ -123,7 +122,7 @@ def main():
     U = torch.empty((c, c), dtype=torch.float32, device="cuda")
     d = torch.empty(c, dtype=torch.float32, device="cuda")
     info = torch.zeros(1, dtype=torch.int32, device="cuda")
-    grid = torch.empty(hx.grid_shape(P, r, c), dtype=torch.float32, device="cuda")
+    grid = torch.empty(lq.grid_shape(P, r, c), dtype=torch.float32, device="cuda")
     Wq = torch.empty_like(W)
     codes = torch.empty((r, c), dtype=torch.uint8, device="cuda")
     row_loss = torch.empty(r, dtype=torch.float32, device="cuda")

@@ -117,6 +117,33 @@ def _ld(t: torch.Tensor, name: str) -> int:
     return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
 
 
+def _dense(t: Optional[torch.Tensor], shape, name: str) -> None:
+    """The C side reads these with their natural leading dimension: refuse views."""
+    if t is None:
+        return
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+
+
+def grid_shape(P: "lq_params", r: int, c: int):
+    """Shape of the grid tensor lq_fit_grid writes for P: [r x 2^b] or [r x c/group x 2]."""
+    if P.mode == LQ_GRID_NONUNIFORM:
+        return (r, 1 << P.bits)
+    g = P.group_size if P.group_size > 0 else c
+    return (r, c // g, 2)
+
+
+def params_for(cfg, **overrides) -> "lq_params":
+    """lq_params from any object with the fields mode ("nu" / "aff"), bits, group_size, block,
+    damp, p, T (such as a layer configuration of lq_synth)."""
+    kw = dict(bits=cfg.bits, mode=LQ_GRID_AFFINE if cfg.mode == "aff" else LQ_GRID_NONUNIFORM,
+              group_size=cfg.group_size, block=cfg.block, damp=cfg.damp, p=cfg.p, T=cfg.T)
+    kw.update(overrides)
+    return lq_params_default(**kw)
+
+
 def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
@@ -179,6 +206,7 @@ def lq_cholesky_inv(H: torch.Tensor, damp: float, U: torch.Tensor, hinv_diag: to
                     info: torch.Tensor, ws: torch.Tensor) -> None:
     c = H.shape[0]
     wp, wn = _ws(ws)
+    _dense(hinv_diag, (c,), "hinv_diag")
     _check(load().lq_cholesky_inv(_ptr(H, torch.float32, "H"), _ld(H, "H"), c, float(damp),
                                   _ptr(U, torch.float32, "U"), _ld(U, "U"),
                                   _ptr(hinv_diag, torch.float32, "hinv_diag"),
@@ -189,6 +217,8 @@ def lq_fit_grid(W: torch.Tensor, hinv_diag: torch.Tensor, P: lq_params, grid: to
                 ws: torch.Tensor) -> None:
     r, c = W.shape
     wp, wn = _ws(ws)
+    _dense(hinv_diag, (c,), "hinv_diag")
+    _dense(grid, grid_shape(P, r, c), "grid")
     _check(load().lq_fit_grid(_ptr(W, torch.float32, "W"), r, c, _ld(W, "W"),
                               _ptr(hinv_diag, torch.float32, "hinv_diag"), ctypes.byref(P),
                               _ptr(grid, torch.float32, "grid"), wp, wn, _stream()))
@@ -198,8 +228,9 @@ def lq_fit_grid_from(W: torch.Tensor, hinv_diag: torch.Tensor, P: lq_params,
                      init_grid: Optional[torch.Tensor], grid: torch.Tensor, ws: torch.Tensor) -> None:
     r, c = W.shape
     wp, wn = _ws(ws)
-    if init_grid is not None and not init_grid.is_contiguous():
-        raise ValueError("init_grid must be contiguous")
+    _dense(hinv_diag, (c,), "hinv_diag")
+    _dense(grid, grid_shape(P, r, c), "grid")
+    _dense(init_grid, grid_shape(P, r, c), "init_grid")
     _check(load().lq_fit_grid_from(_ptr(W, torch.float32, "W"), r, c, _ld(W, "W"),
                                    _ptr(hinv_diag, torch.float32, "hinv_diag"), ctypes.byref(P),
                                    _ptr(init_grid, torch.float32, "init_grid"),
@@ -211,6 +242,9 @@ def lq_kmeanspp_seed(W: torch.Tensor, hinv_diag: torch.Tensor, P: lq_params, u: 
     """k-means++ seeding of the non-uniform grids; u [r x 2^b] float64 uniforms in [0, 1)."""
     r, c = W.shape
     wp, wn = _ws(ws)
+    _dense(hinv_diag, (c,), "hinv_diag")
+    _dense(u, (r, 1 << P.bits), "u")
+    _dense(grid_init, (r, 1 << P.bits), "grid_init")
     _check(load().lq_kmeanspp_seed(_ptr(W, torch.float32, "W"), r, c, _ld(W, "W"),
                                    _ptr(hinv_diag, torch.float32, "hinv_diag"), ctypes.byref(P),
                                    _ptr(u, torch.float64, "u"), _ptr(grid_init, torch.float32, "grid_init"),
@@ -221,6 +255,9 @@ def lq_quantize_layer(W: torch.Tensor, U: torch.Tensor, grid: torch.Tensor, P: l
                       codes: torch.Tensor, row_loss: Optional[torch.Tensor], ws: torch.Tensor) -> None:
     r, c = W.shape
     wp, wn = _ws(ws)
+    _dense(grid, grid_shape(P, r, c), "grid")
+    _dense(codes, (r, c), "codes")
+    _dense(row_loss, (r,), "row_loss")
     _check(load().lq_quantize_layer(_ptr(W, torch.float32, "W"), r, c, _ld(W, "W"),
                                     _ptr(U, torch.float32, "U"), _ld(U, "U"),
                                     _ptr(grid, torch.float32, "grid"), ctypes.byref(P),
@@ -233,6 +270,10 @@ def lq_quantize_exact(W: torch.Tensor, Hinv: torch.Tensor, grid: torch.Tensor, P
                       row_loss: Optional[torch.Tensor], ws: torch.Tensor) -> None:
     r, c = W.shape
     wp, wn = _ws(ws)
+    _dense(grid, grid_shape(P, r, c), "grid")
+    _dense(codes, (r, c), "codes")
+    _dense(order, (r, c), "order")
+    _dense(row_loss, (r,), "row_loss")
     _check(load().lq_quantize_exact(_ptr(W, torch.float32, "W"), r, c, _ld(W, "W"),
                                     _ptr(Hinv, torch.float64, "Hinv"), _ld(Hinv, "Hinv"),
                                     _ptr(grid, torch.float32, "grid"), ctypes.byref(P),

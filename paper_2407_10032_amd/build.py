@@ -21,11 +21,11 @@ FLAGS = [
 ]
 
 
-_COL_HEADERS = ("lq_quantize_col.h", "lq_common.h")
+_COL_HEADERS = ("lq_quantize_col.h", "lq_common.h", "lq_mfma.h")
 
 
 def _newest_header(src: str) -> float:
-    """Newest header the source can depend on (the column-kernel units use only two)."""
+    """Newest header the source can depend on (the column-kernel units use only three)."""
     names = _COL_HEADERS if src.startswith("quantize_col") else tuple(
         f for f in os.listdir(CSRC) if f.endswith(".h"))
     paths = [os.path.join(CSRC, f) for f in names] + [os.path.join(HERE, "..", "include", "leanquant.h")]

@@ -695,8 +695,8 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
   const int nb = plan.nb;
 
   const size_t potrf_lds = (NB * DLD + 13 * 32 * 33 + 4 * 32 * 32 + 64 + 128) * sizeof(float);
-  static bool attr_done = false;
-  if (!attr_done) {
+  static lq::DeviceOnce attr_once;
+  if (lq::DeviceOnceGuard once(attr_once); once.first()) {
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)potrf_diag_kernel,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)potrf_lds));
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)chol_small_kernel<CH_PANEL>,
@@ -707,7 +707,7 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)chol_small_lds<CH_TRI_ROW>()));
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)chol_small_kernel<CH_TRI_UPD>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)chol_small_lds<CH_TRI_UPD>()));
-    attr_done = true;
+    once.done();
   }
 
   hipLaunchKernelGGL(diag_mean_kernel, dim3(1), dim3(1024), 0, st, H, ldh, c, damp, scal, info);
@@ -768,6 +768,8 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
     if (i + 1 < nb) return launch(CH_TRI_UPD, (nb - i - 1) * (i + 1), sinv, b);
     return LQ_OK;
   };
+  // (a lambda, so that a failing launch in the middle still joins the side stream below)
+  auto factor_chain = [&]() -> lq_status {
   for (int kb = 0; kb < nb; ++kb) {
     hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(256), potrf_lds, st, A, cp, kb, Dinv, info, c);
     LQ_CHECK_LAUNCH("potrf_diag_kernel");
@@ -790,10 +792,19 @@ extern "C" lq_status lq_cholesky_inv(const float* H, int64_t ldh, int64_t c, flo
       if (ss != LQ_OK) return ss;
     }
   }
+  return LQ_OK;
+  };
+  const lq_status chain_rc = factor_chain();
   if (side) {
-    LQ_CHECK_HIP(hipEventRecord(side->join, side->stream));
-    LQ_CHECK_HIP(hipStreamWaitEvent(st, side->join, 0));
+    // joined also after an error: whatever reached the side stream stays ordered before the
+    // caller's later work on `stream`
+    const hipError_t e1 = hipEventRecord(side->join, side->stream);
+    const hipError_t e2 = hipStreamWaitEvent(st, side->join, 0);
+    if (chain_rc != LQ_OK) return chain_rc;
+    LQ_CHECK_HIP(e1);
+    LQ_CHECK_HIP(e2);
   } else {
+    if (chain_rc != LQ_OK) return chain_rc;
     for (int i = 0; i < nb; ++i) {
       lq_status si = inverse_step(i);
       if (si != LQ_OK) return si;

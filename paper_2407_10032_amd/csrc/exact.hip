@@ -89,10 +89,14 @@ __global__ __launch_bounds__(NT) void exact_rows_kernel(ExactArgs a) {
 
     for (int step = 0; step < c; ++step) {
       // (a) smallest loss error among the weights this thread looks at
+      // (bi starts at the first weight still to do that this thread sees, so that the pick is a
+      // valid index even when every score is NaN or infinite: non-finite input then gives a
+      // meaningless but complete order instead of an access outside the row)
       double bs = INFINITY;
       int bi = 0x7fffffff;
       for (int k = tid; k < c; k += NT) {
         if (!sdone[k]) {
+          if (bi == 0x7fffffff) bi = k;
           double q; int code;
           quant1(sw[k], sG, K, a.aff, S, Z, qmax, q, code);
           const double dq = q - sw[k];
@@ -109,7 +113,9 @@ __global__ __launch_bounds__(NT) void exact_rows_kernel(ExactArgs a) {
         }
         __syncthreads();
       }
-      const int i = sRedI[0];
+      // one weight is still to do in every step, so the reduction holds a valid index; the
+      // clamp only keeps every access below inside the row whatever the input
+      const int i = min(sRedI[0], c - 1);
       if (tid == 0) {
         double q; int code;
         quant1(sw[i], sG, K, a.aff, S, Z, qmax, q, code);
@@ -213,11 +219,11 @@ extern "C" lq_status lq_quantize_exact(float* W, int64_t r, int64_t c, int64_t l
   a.slots = (double*)ws;
   a.bits = P->bits; a.aff = (P->mode == LQ_GRID_AFFINE);
   const size_t lds = (size_t)c * (3 * sizeof(double) + 1) + 16;
-  static bool attr_done = false;
-  if (!attr_done) {
+  static lq::DeviceOnce attr_once;
+  if (lq::DeviceOnceGuard once(attr_once); once.first()) {
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)exact_rows_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)(MAX_C * 25 + 16)));
-    attr_done = true;
+    once.done();
   }
   hipLaunchKernelGGL(exact_rows_kernel, dim3((unsigned)exact_slots(r)), dim3(NT), lds, (hipStream_t)stream, a);
   LQ_CHECK_LAUNCH("exact_rows_kernel");

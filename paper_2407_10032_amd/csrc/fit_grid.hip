@@ -453,15 +453,15 @@ lq_status fit_grid_impl(const float* W, int64_t r, int64_t c, int64_t ldw, const
       if (padded < best) { best = padded; nta = cand; }
     }
   }
-  static bool attr_done = false;
-  if (!attr_done) {
+  static lq::DeviceOnce attr_once;
+  if (lq::DeviceOnceGuard once(attr_once); once.first()) {
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)affine_search_kernel<64>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)(8192 * 16)));
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)affine_search_kernel<128>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)(8192 * 16)));
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)affine_search_kernel<256>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)(8192 * 16)));
-    attr_done = true;
+    once.done();
   }
   const dim3 ggrid((unsigned)(r * ngroups));
 #define LQ_AFF(N) hipLaunchKernelGGL(affine_search_kernel<N>, ggrid, dim3(N), lds, st, W, c, ldw, (int)g, \

@@ -95,13 +95,13 @@ static lq_status accumulate_device(float* H, int64_t ldh, const float* X, int64_
   const bool vec = (ldx % 4 == 0) && lq::aligned(X, 16);
   const size_t lds = 4 * KT * lq::TILE * sizeof(float);
   dim3 grid((unsigned)((int64_t)plan.splits * plan.ntiles)), block(lq::WG_THREADS);
-  static bool attr_done = false;
-  if (!attr_done) {
+  static lq::DeviceOnce attr_once;
+  if (lq::DeviceOnceGuard once(attr_once); once.first()) {
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, true, true, true, MINW>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, true, true, false, MINW>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_done = true;
+    once.done();
   }
   if (vec)
     hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, true, true, true, MINW>), grid, block, lds, st, a);
@@ -169,6 +169,8 @@ extern "C" lq_status lq_hessian_accumulate_host(float* H, int64_t ldh, const flo
   LQ_CHECK_HIP(hipEventRecord(side->fork[2], st));
   LQ_CHECK_HIP(hipStreamWaitEvent(side->stream, side->fork[2], 0));
   const int64_t nchunks = lq::ceil_div(n_tokens, chunk_tokens);
+  // (a lambda, so that an error in the middle still joins the copy stream below)
+  auto chunk_chain = [&]() -> lq_status {
   for (int64_t k = 0; k < nchunks; ++k) {
     const int64_t t0 = k * chunk_tokens;
     const int64_t nt = (n_tokens - t0) < chunk_tokens ? (n_tokens - t0) : chunk_tokens;
@@ -189,4 +191,11 @@ extern "C" lq_status lq_hessian_accumulate_host(float* H, int64_t ldh, const flo
     if (k + 2 < nchunks) LQ_CHECK_HIP(hipEventRecord(side->fork[k & 1], st));
   }
   return LQ_OK;
+  };
+  const lq_status rc = chunk_chain();
+  if (rc != LQ_OK) {
+    // a copy may be in flight that `stream` has not been told to wait for: join it
+    if (hipEventRecord(side->join, side->stream) == hipSuccess) (void)hipStreamWaitEvent(st, side->join, 0);
+  }
+  return rc;
 }

@@ -7,6 +7,8 @@
 #include <stdint.h>
 #include <stdio.h>
 
+#include <mutex>
+
 #include "../../include/leanquant.h"
 
 namespace lq {
@@ -30,6 +32,31 @@ struct SideStream {
   hipEvent_t join;      // recorded on the side stream, waited on by the caller's stream
 };
 SideStream* side_stream(int which = 0);   // which: 0 or 1
+
+// One-time set-up per device (kernel attributes such as the dynamic LDS limit), safe when
+// several host threads enter a call for the first time together and when one process drives
+// several devices.  Usage:
+//   static lq::DeviceOnce once_flag;
+//   if (lq::DeviceOnceGuard once(once_flag); once.first()) { ...set up...; once.done(); }
+// The guard holds the flag's mutex for its lifetime; a set-up that fails (early return) is
+// tried again by the next call.
+constexpr int MAX_DEVICES = 16;
+struct DeviceOnce {
+  std::mutex m;
+  bool done[MAX_DEVICES] = {};
+};
+class DeviceOnceGuard {
+ public:
+  explicit DeviceOnceGuard(DeviceOnce& o) : o_(o), lk_(o.m) {
+    if (hipGetDevice(&dev_) != hipSuccess || dev_ < 0 || dev_ >= MAX_DEVICES) dev_ = -1;
+  }
+  bool first() const { return dev_ < 0 || !o_.done[dev_]; }
+  void done() { if (dev_ >= 0) o_.done[dev_] = true; }
+ private:
+  DeviceOnce& o_;
+  std::unique_lock<std::mutex> lk_;
+  int dev_ = -1;
+};
 
 // Resolve Eq. 8's shrink limit t for the given parameters; returns < 0 if invalid.
 int resolve_t(const lq_params* P);

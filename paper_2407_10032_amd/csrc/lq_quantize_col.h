@@ -36,6 +36,7 @@ struct ColArgs {
   float* row_loss;      // may be null
   int first;            // 1 for the first block (row_loss starts from zero)
   int vecw;             // W rows are 16-byte aligned (ldw % 4 == 0)
+  int vecc;             // rows of codes are 4-byte aligned (base pointer and c)
 };
 
 // Nearest point of an ascending grid; ties go to the lower point.  code = number of
@@ -224,7 +225,7 @@ __global__ __launch_bounds__(QT) void column_block_kernel(ColArgs a, const float
     for (int k = 0; k < SB; ++k) sW[lane * LD + cb + k] = ws[k];
     if (valid) {
       uint8_t* cout = a.codes + row * a.c + a.i0 + cb;
-      if (cb + SB <= nb && ((a.c | a.i0) % 4) == 0) {
+      if (cb + SB <= nb && a.vecc && (a.i0 % 4) == 0) {
 #pragma unroll
         for (int q4 = 0; q4 < SB / 4; ++q4) reinterpret_cast<uint32_t*>(cout)[q4] = pk[q4];
       } else {
@@ -308,11 +309,11 @@ lq_status launch_column(const ColArgs& a, const float* ud, const float* urinv, c
   dim3 grid((unsigned)lq::ceil_div(a.r, QT)), block(QT);
 #define LQ_COL(BITS, AFF)                                                                          \
   do {                                                                                             \
-    static bool done = false;                                                                      \
-    if (!done) {                                                                                   \
+    static lq::DeviceOnce attr_once;                                                               \
+    if (lq::DeviceOnceGuard once(attr_once); once.first()) {                                       \
       LQ_CHECK_HIP(hipFuncSetAttribute((const void*)column_block_kernel<B, BITS, AFF>,             \
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));     \
-      done = true;                                                                                 \
+      once.done();                                                                                 \
     }                                                                                              \
     hipLaunchKernelGGL((column_block_kernel<B, BITS, AFF>), grid, block, lds, st, a, ud, urinv);   \
   } while (0)

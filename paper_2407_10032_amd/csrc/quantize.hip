@@ -102,15 +102,16 @@ extern "C" lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t l
   a.Et = (float*)ws; a.rpad = rpad;
   a.row_loss = row_loss;
   a.vecw = (ldw % 4 == 0) && lq::aligned(W, 16);
+  a.vecc = (c % 4 == 0) && lq::aligned(codes, 4);
 
   const size_t gemm_lds = 4 * KT * lq::TILE * sizeof(float);
-  static bool attr_done = false;
-  if (!attr_done) {
+  static lq::DeviceOnce attr_once;
+  if (lq::DeviceOnceGuard once(attr_once); once.first()) {
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, false, false, true, MINW>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds));
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, false, false, false, MINW>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds));
-    attr_done = true;
+    once.done();
   }
 
   hipLaunchKernelGGL(pack_diag_blocks_kernel, dim3((unsigned)plan.nblk), dim3(256), 0, st, U, ldu, c, B,

@@ -166,11 +166,11 @@ extern "C" lq_status lq_kmeanspp_seed(const float* W, int64_t r, int64_t c, int6
   const int K = 1 << P->bits;
   const size_t lds = (size_t)c * sizeof(float);
   const dim3 grid((unsigned)(r < 8192 ? r : 8192)), block(NT);
-  static bool attr_done = false;
-  if (!attr_done) {
+  static lq::DeviceOnce attr_once;
+  if (lq::DeviceOnceGuard once(attr_once); once.first()) {
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)kmeanspp_rows_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * NT * 4));
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)kmeanspp_rows_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * NT * 4));
-    attr_done = true;
+    once.done();
   }
   if (c <= 16 * NT)
     hipLaunchKernelGGL(kmeanspp_rows_kernel<16>, grid, block, lds, st, W, r, c, ldw, (const double*)om64, u, K, grid_init);

@@ -15,11 +15,8 @@ def to_dev(a, dtype=torch.float32):
     return torch.from_numpy(np.ascontiguousarray(a)).to(DEV, dtype=dtype)
 
 
-def params_for(cfg, **over):
-    kw = dict(bits=cfg.bits, mode=lq.LQ_GRID_AFFINE if cfg.mode == "aff" else lq.LQ_GRID_NONUNIFORM,
-              group_size=cfg.group_size, block=cfg.block, damp=cfg.damp, p=cfg.p, T=cfg.T)
-    kw.update(over)
-    return lq.lq_params_default(**kw)
+params_for = lq.params_for
+grid_shape = lq.grid_shape
 
 
 def gpu_hessian(x_chunks, c):
@@ -45,13 +42,6 @@ def gpu_cholesky(H, damp):
     lq.lq_cholesky_inv(H, damp, U, d, info, ws)
     torch.cuda.synchronize()
     return U, d, int(info.item())
-
-
-def grid_shape(P, r, c):
-    if P.mode == lq.LQ_GRID_NONUNIFORM:
-        return (r, 2 ** P.bits)
-    g = P.group_size if P.group_size > 0 else c
-    return (r, c // g, 2)
 
 
 def gpu_fit_grid(W, d, P, init=None):
