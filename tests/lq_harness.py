@@ -97,3 +97,52 @@ def aff_grid_match(SZ_gpu, SZ_ref, rtol=1e-4):
 
 def code_agreement(codes_gpu, codes_ref):
     return float(np.mean(codes_gpu.astype(np.int64) == codes_ref.astype(np.int64)))
+
+
+def compare_rows_strict(mode, bits, W_rows, d, U64, grid_g, codes_g, grid_ref, codes_ref, p=4.0,
+                        group_size=0, B=128, say=print):
+    """Grid and code check of EVERY sampled row against the float64 oracle.
+
+    A row whose grid equals the oracle's (1e-4 relative; affine: every group's S within 1e-4
+    and the same integer Z) has its codes compared with the oracle's codes.  A row whose grid
+    differs must carry an equally good grid -- Eq. 5 objective of the row within 1e-3 of the
+    oracle's (non-uniform), Eq. 7 objective of every differing group within 1e-5 (affine), both
+    evaluated in float64 -- and its codes are compared with the oracle's column loop run from
+    the DEVICE's grid for that row (rows are independent problems, Eq. 1).  Asserts the
+    objective rule; returns (share of rows / groups with the oracle's grid, pooled code
+    agreement over all rows, number of rows re-run from the device's grid).
+    """
+    from oracle import leanquant_oracle as orc
+
+    W64 = np.asarray(W_rows, dtype=np.float64)
+    om = orc.importance(d, p)
+    gg = np.asarray(grid_g, dtype=np.float64)
+    if mode == "nu":
+        row_ok = nu_grid_match(gg, grid_ref)
+        share = float(row_ok.mean())
+        if (~row_ok).any():
+            og = orc.eq5_objective(W64[~row_ok], om, gg[~row_ok])
+            orf = orc.eq5_objective(W64[~row_ok], om, np.asarray(grid_ref)[~row_ok])
+            say(f"    {int((~row_ok).sum())} rows with another grid: Eq. 5 objective ratios {np.array2string(og / orf, precision=6)}")
+            assert np.all(og <= orf * (1 + 1e-3)), (og / orf)
+    else:
+        g = group_size if group_size else W64.shape[1]
+        m = aff_grid_match(gg, grid_ref)
+        row_ok = m.all(axis=1)
+        share = float(m.mean())
+        worst = 0.0
+        for k, gi in zip(*np.nonzero(~m)):
+            sl = slice(gi * g, (gi + 1) * g)
+            og = orc.eq7_objective(W64[k, sl], om[sl], float(gg[k, gi, 0]), float(gg[k, gi, 1]), bits)
+            orf = orc.eq7_objective(W64[k, sl], om[sl], float(grid_ref[k, gi, 0]), float(grid_ref[k, gi, 1]), bits)
+            worst = max(worst, og / orf - 1.0)
+            assert og <= orf * (1 + 1e-5), (k, gi, og, orf)
+        if (~m).any():
+            say(f"    {int((~m).sum())} groups with another (S, Z): worst Eq. 7 objective excess {worst:.2e}")
+    ref_codes = np.array(codes_ref, dtype=np.int64, copy=True)
+    redo = np.nonzero(~row_ok)[0]
+    if redo.size:
+        _, c2, _ = orc.quantize_layer(W64[redo], U64, gg[redo], mode, bits, group_size=group_size, B=B)
+        ref_codes[redo] = c2
+    agree = code_agreement(np.asarray(codes_g), ref_codes)
+    return share, agree, int(redo.size)

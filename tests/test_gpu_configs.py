@@ -7,8 +7,11 @@ seeded sample of rows, which is exact because rows are independent problems (Eq.
 Configurations 3-5 keep their real column count and structure; the token count (the
 reduction length of the Gram product) is cut to a quarter or half and the row count of the
 two largest layers is reduced, so that the float64 oracle finishes in about a minute each.
-Fewer tokens make H worse conditioned than in the real layer, i.e. the test is harder.  Bars: codes >= 99.9 %,
-grids within 1e-4 relative, sampled-row layer loss within 1e-3 relative.
+Fewer tokens make H worse conditioned than in the real layer, i.e. the test is harder.  Bars: every
+sampled row is checked: grids within 1e-4 relative on all rows but at most one (non-uniform) or on
+>= 99 % of the groups (affine), any other grid must be equally good by its Eq. 5 / Eq. 7
+objective in float64 (1e-3 / 1e-5) and is followed through the oracle's column loop; codes
+>= 99.9 % over all sampled rows; sampled-row layer loss within 1e-3 relative.
 """
 import time
 
@@ -70,21 +73,17 @@ def _check_hud(Hg, Ug, dg, H, U, d, n_tokens):
     assert uerr < 5e-5 and derr < 5e-5
 
 
-def _compare_rows(cfg, P, W_rows, H, ref, grid_g, What_g, codes_g):
-    """Grid match per row, code agreement over the rows whose grid matches (a different but
-    equally good grid legitimately gives other codes), loss ratio over all sampled rows."""
-    if cfg.mode == "nu":
-        row_ok = hx.nu_grid_match(grid_g, ref["grid"])
-        gok = row_ok.mean()
-    else:
-        m = hx.aff_grid_match(grid_g, ref["grid"])
-        row_ok = m.all(axis=1)
-        gok = m.mean()
-    agree = hx.code_agreement(codes_g[row_ok], ref["codes"][row_ok]) if row_ok.any() else 0.0
+def _compare_rows(cfg, P, W_rows, H, U, d, ref, grid_g, What_g, codes_g):
+    """Every sampled row gets a grid check and a code check (hx.compare_rows_strict: rows whose
+    grid differs from the oracle's must carry an equally good one and are compared with the
+    oracle's column loop run from the device's grid); loss ratio over all sampled rows."""
+    gok, agree, redone = hx.compare_rows_strict(cfg.mode, cfg.bits, W_rows, d, U, grid_g, codes_g, ref["grid"],
+                                                ref["codes"], p=cfg.p, group_size=P.group_size, B=cfg.block,
+                                                say=_say)
     l_gpu = orc.layer_loss(W_rows, What_g, H)
     l_ref = orc.layer_loss(W_rows, ref["W_hat"], H)
-    _say(f"    grids matching {gok:.4f} ({int(row_ok.sum())}/{row_ok.size} rows entirely), codes equal on those "
-         f"rows {agree:.5f}, loss gpu/ref {l_gpu / l_ref:.6f}")
+    _say(f"    grids matching {gok:.5f}, codes equal over all {len(W_rows)} rows {agree:.5f} "
+         f"({redone} rows re-run from the device's grid), loss gpu/ref {l_gpu / l_ref:.6f}")
     return gok, agree, l_gpu / l_ref
 
 
@@ -102,9 +101,9 @@ def test_config2_full_size():
     G = orc.fit_grid_nu(W_rows, d, cfg.bits, cfg.p)
     What, codes_ref, loss_ref = orc.quantize_layer(W_rows, U, G, "nu", cfg.bits, B=cfg.block)
     ref = dict(grid=G, W_hat=What, codes=codes_ref)
-    gok, agree, lr = _compare_rows(cfg, P, W_rows, H, ref, grid.cpu().numpy()[rows],
+    gok, agree, lr = _compare_rows(cfg, P, W_rows, H, U, d, ref, grid.cpu().numpy()[rows],
                                    Wq.cpu().numpy()[rows], codes.cpu().numpy()[rows])
-    assert gok >= 0.99 and agree >= 0.999 and abs(lr - 1.0) < 1e-3
+    assert (1.0 - gok) * rows.size <= 1.0 + 1e-9 and agree >= 0.999 and abs(lr - 1.0) < 1e-3
     rl = row_loss.cpu().numpy()[rows]
     assert abs(rl.sum() / loss_ref.sum() - 1.0) < 2e-3
     # property at full size: every code indexes the row's grid and W_hat is that grid point
@@ -126,9 +125,9 @@ def test_config3_shape_nonuniform_3bit():
     W_rows = lq_synth.weights(cfg, rows)
     G = orc.fit_grid_nu(W_rows, d, cfg.bits, cfg.p)
     What, codes_ref, _ = orc.quantize_layer(W_rows, U, G, "nu", cfg.bits, B=cfg.block)
-    gok, agree, lr = _compare_rows(cfg, P, W_rows, H, dict(grid=G, W_hat=What, codes=codes_ref),
+    gok, agree, lr = _compare_rows(cfg, P, W_rows, H, U, d, dict(grid=G, W_hat=What, codes=codes_ref),
                                    grid.cpu().numpy()[rows], Wq.cpu().numpy()[rows], codes.cpu().numpy()[rows])
-    assert gok >= 0.98 and agree >= 0.999 and abs(lr - 1.0) < 1e-3
+    assert (1.0 - gok) * rows.size <= 1.0 + 1e-9 and agree >= 0.999 and abs(lr - 1.0) < 1e-3
 
 
 def test_config4_shape_affine_group128():
@@ -139,15 +138,15 @@ def test_config4_shape_affine_group128():
     H = _oracle_hessian(cfg)
     U, d = orc.cholesky_inv(H, cfg.damp)
     _check_hud(Hg.cpu().numpy(), Ug.cpu().numpy(), dg.cpu().numpy(), H, U, d, cfg.n_tokens)
-    rows = lq_synth.sample_rows(cfg, 2)
+    rows = lq_synth.sample_rows(cfg, 8)
     W_rows = lq_synth.weights(cfg, rows)
     t0 = time.time()
     SZ = orc.fit_grid_aff(W_rows, d, cfg.bits, cfg.p, group_size=cfg.group_size, T=cfg.T)
     _say(f"    oracle affine search on {rows.size} rows: {time.time() - t0:.0f} s")
     What, codes_ref, _ = orc.quantize_layer(W_rows, U, SZ, "aff", cfg.bits, group_size=cfg.group_size, B=cfg.block)
-    gok, agree, lr = _compare_rows(cfg, P, W_rows, H, dict(grid=SZ, W_hat=What, codes=codes_ref),
+    gok, agree, lr = _compare_rows(cfg, P, W_rows, H, U, d, dict(grid=SZ, W_hat=What, codes=codes_ref),
                                    grid.cpu().numpy()[rows], Wq.cpu().numpy()[rows], codes.cpu().numpy()[rows])
-    assert gok >= 0.95 and agree >= 0.999 and abs(lr - 1.0) < 2e-3
+    assert gok >= 0.99 and agree >= 0.999 and abs(lr - 1.0) < 1e-3
 
 
 def test_config5_shape_both_modes():
@@ -166,9 +165,9 @@ def test_config5_shape_both_modes():
     W_rows = lq_synth.weights(cfg, rows)
     G = orc.fit_grid_nu(W_rows, d, cfg.bits, cfg.p)
     What, codes_ref, _ = orc.quantize_layer(W_rows, U, G, "nu", cfg.bits, B=cfg.block)
-    gok, agree, lr = _compare_rows(cfg, P, W_rows, H, dict(grid=G, W_hat=What, codes=codes_ref),
+    gok, agree, lr = _compare_rows(cfg, P, W_rows, H, U, d, dict(grid=G, W_hat=What, codes=codes_ref),
                                    grid.cpu().numpy()[rows], Wq.cpu().numpy()[rows], codes.cpu().numpy()[rows])
-    assert gok >= 0.95 and agree >= 0.999 and abs(lr - 1.0) < 1e-3
+    assert (1.0 - gok) * rows.size <= 1.0 + 1e-9 and agree >= 0.999 and abs(lr - 1.0) < 1e-3
     del grid, Wq, codes
 
     # 2-bit affine, group 64: grid parity at T = 2048 on sampled groups, end to end at T = 256
@@ -180,7 +179,7 @@ def test_config5_shape_both_modes():
     g = np.random.default_rng(77)
     W_all = lq_synth.weights(cfa, rows[:4])
     n_ok = 0
-    picks = [(int(k), int(gi)) for k in range(4) for gi in g.choice(cfa.c // 64, size=6, replace=False)]
+    picks = [(int(k), int(gi)) for k in range(4) for gi in g.choice(cfa.c // 64, size=16, replace=False)]
     t0 = time.time()
     for k, gi in picks:
         sl = slice(gi * 64, (gi + 1) * 64)
@@ -191,14 +190,14 @@ def test_config5_shape_both_modes():
         else:
             assert orc.eq7_objective(W_all[k, sl], om[sl], Sg, Zg, 2) <= loss * (1 + 1e-5)
     _say(f"    affine T=2048: {n_ok}/{len(picks)} sampled groups identical ({time.time() - t0:.0f} s of oracle)")
-    assert n_ok >= len(picks) - 2
+    assert n_ok >= 0.9 * len(picks)
     Pb = hx.params_for(cfa, T=256)
     gridb = hx.gpu_fit_grid(Wd, dg, Pb)
     Wq, codes, _ = hx.gpu_quantize(Wd, Ug, gridb, Pb)
-    rb = rows[:6]
+    rb = rows[:8]
     W_rows = lq_synth.weights(cfa, rb)
     SZ = orc.fit_grid_aff(W_rows, d, 2, cfa.p, group_size=64, T=256)
     What, codes_ref, _ = orc.quantize_layer(W_rows, U, SZ, "aff", 2, group_size=64, B=cfa.block)
-    gok, agree, lr = _compare_rows(cfa, Pb, W_rows, H, dict(grid=SZ, W_hat=What, codes=codes_ref),
+    gok, agree, lr = _compare_rows(cfa, Pb, W_rows, H, U, d, dict(grid=SZ, W_hat=What, codes=codes_ref),
                                    gridb.cpu().numpy()[rb], Wq.cpu().numpy()[rb], codes.cpu().numpy()[rb])
-    assert gok >= 0.99 and agree >= 0.999 and abs(lr - 1.0) < 2e-3
+    assert gok >= 0.995 and agree >= 0.999 and abs(lr - 1.0) < 1e-3

@@ -97,7 +97,7 @@ def test_non_uniform_configurations_at_full_size(name):
     _say(f"  fit + loop on all rows done ({time.time() - t0:.0f} s)")
 
     # ---- sampled rows against the oracle, from the device's d and U
-    rows = np.sort(rng.choice(r, size=12, replace=False))
+    rows = np.sort(rng.choice(r, size=16, replace=False))
     Wr = W[rows].cpu().numpy()
     U64 = Ucpu.astype(np.float64)
     Gref = orc.fit_grid_nu(Wr, dcpu, cfg.bits, cfg.p)
@@ -105,9 +105,12 @@ def test_non_uniform_configurations_at_full_size(name):
     ok = hx.nu_grid_match(Gg, Gref)
     What_ref, codes_ref, loss_ref = orc.quantize_layer(Wr, U64, Gref, "nu", cfg.bits, B=cfg.block)
     cg = codes[rows].cpu().numpy()
-    agree = hx.code_agreement(cg[ok], codes_ref[ok]) if ok.any() else 0.0
-    _say(f"  sampled rows: grids matching {ok.mean():.3f}, codes equal {agree:.5f} ({time.time() - t0:.0f} s)")
-    assert ok.mean() >= 0.9
+    # every sampled row: the oracle's grid, or an equally good one followed through the oracle's loop
+    share, agree, redone = hx.compare_rows_strict("nu", cfg.bits, Wr, dcpu, U64, Gg, cg, Gref, codes_ref,
+                                                  p=cfg.p, B=cfg.block, say=_say)
+    _say(f"  sampled rows: grids matching {share:.3f}, codes equal over all {len(rows)} rows {agree:.5f} "
+         f"({redone} re-run from the device's grid) ({time.time() - t0:.0f} s)")
+    assert (~ok).sum() <= 1
     assert agree >= 0.999
     # energy identity for the device's own result (Eq. 3 summed over the row)
     Whr = What[rows].cpu().numpy().astype(np.float64)
@@ -159,7 +162,7 @@ def test_config4_affine_full_size():
     assert bool(torch.all(torch.isfinite(row_loss))) and bool(torch.all(row_loss >= 0))
     # the search can only improve on the plain min-max grid of the same group (candidate (0, 0))
     rng = np.random.default_rng(4242)
-    rows = np.sort(rng.choice(r, size=2, replace=False))
+    rows = np.sort(rng.choice(r, size=8, replace=False))
     Wr = W[rows].cpu().numpy()
     dcpu = d.cpu().numpy()
     t1 = time.time()
@@ -167,24 +170,20 @@ def test_config4_affine_full_size():
     _say(f"  oracle affine search on {rows.size} rows: {time.time() - t1:.0f} s")
     SZg = SZ[rows].cpu().numpy()
     ok = hx.aff_grid_match(SZg, SZref)
-    om = orc.importance(dcpu, cfg.p)
-    for k, gi in zip(*np.nonzero(~ok)):
-        sl = slice(gi * g, (gi + 1) * g)
-        got = orc.eq7_objective(Wr[k, sl], om[sl], float(SZg[k, gi, 0]), float(SZg[k, gi, 1]), cfg.bits)
-        ref = orc.eq7_objective(Wr[k, sl], om[sl], float(SZref[k, gi, 0]), float(SZref[k, gi, 1]), cfg.bits)
-        assert got <= ref * (1 + 1e-5)
-    _say(f"  sampled groups identical: {ok.mean():.4f}")
-    assert ok.mean() >= 0.97
+    U64 = U.cpu().numpy().astype(np.float64)
+    _, codes_ref, loss_ref = orc.quantize_layer(Wr, U64, SZref, "aff", cfg.bits, group_size=g, B=cfg.block)
+    # every sampled row: groups with another (S, Z) must score within 1e-5 (Eq. 7, float64), and such a
+    # row is compared with the oracle's column loop run from the device's grids
+    share, agree, redone = hx.compare_rows_strict("aff", cfg.bits, Wr, dcpu, U64, SZg, codes[rows].cpu().numpy(),
+                                                  SZref, codes_ref, p=cfg.p, group_size=g, B=cfg.block, say=_say)
+    _say(f"  sampled groups identical: {share:.4f}; codes equal over all {rows.size} rows {agree:.5f} "
+         f"({redone} re-run from the device's grids) ({time.time() - t0:.0f} s)")
+    assert share >= 0.99
+    assert agree >= 0.999
     row_ok = ok.all(axis=1)
     if row_ok.any():
-        U64 = U.cpu().numpy().astype(np.float64)
-        _, codes_ref, loss_ref = orc.quantize_layer(Wr[row_ok], U64, SZref[row_ok], "aff", cfg.bits,
-                                                    group_size=g, B=cfg.block)
-        agree = hx.code_agreement(codes[rows].cpu().numpy()[row_ok], codes_ref)
-        _say(f"  codes equal on rows with identical grids: {agree:.5f} ({time.time() - t0:.0f} s)")
-        assert agree >= 0.999
         rl = row_loss[rows].cpu().numpy()[row_ok]
-        assert np.max(np.abs(rl - loss_ref) / loss_ref) < 1e-3
+        assert np.max(np.abs(rl - loss_ref[row_ok]) / loss_ref[row_ok]) < 1e-3
 
 
 def test_config5_affine_full_size():
@@ -225,7 +224,7 @@ def test_config5_affine_full_size():
     om = orc.importance(dcpu, cfg.p)
     t_lim = orc.shrink_steps(cfg.bits, cfg.T)
     same = 0
-    picks = [(int(rng.integers(r)), int(rng.integers(c // g))) for _ in range(16)]
+    picks = [(int(rng.integers(r)), int(rng.integers(c // g))) for _ in range(64)]
     for k, gi in picks:
         sl = slice(gi * g, (gi + 1) * g)
         w = W[k, sl].cpu().numpy()
@@ -237,9 +236,9 @@ def test_config5_affine_full_size():
             got = orc.eq7_objective(w, om[sl], S_g, Z_g, cfg.bits)
             assert got <= loss_ref * (1 + 1e-5), (k, gi, got, loss_ref)
     _say(f"  sampled groups identical: {same} of {len(picks)} ({time.time() - t0:.0f} s)")
-    assert same >= len(picks) - 1
+    assert same >= 0.9 * len(picks)
     # stage D: sampled rows, the oracle's column loop from the device's grids and U
-    rows = np.sort(rng.choice(r, size=4, replace=False))
+    rows = np.sort(rng.choice(r, size=8, replace=False))
     U64 = U.cpu().numpy().astype(np.float64)
     _, codes_ref, loss_ref = orc.quantize_layer(W[rows].cpu().numpy(), U64, SZ[rows].cpu().numpy().astype(np.float64),
                                                 "aff", cfg.bits, group_size=g, B=cfg.block)

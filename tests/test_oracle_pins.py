@@ -285,6 +285,35 @@ def test_tr_loss_monotone_for_diagonal_hessian_p1():
 
 
 # ------------------------------------------------------------------ step 3, affine
+def test_eq5_objective_hand_computed():
+    """Eq. 5 by hand: three weights, two grid points, distinct importance weights.
+    row 0: w = (0.1, 0.4, 0.9), G = (0, 1): nearest points (0, 0, 1), errors (0.1, 0.4, 0.1),
+           omega = (1, 2, 3) -> 1 * 0.01 + 2 * 0.16 + 3 * 0.01 = 0.36
+    row 1: w = (-1, 0.6, 0.5), G = (-1, 0.5): errors (0, 0.1, 0) -> 2 * 0.01 = 0.02
+    (dropping omega would give 0.18 and 0.01; squaring omega 0.92 and 0.04)."""
+    w = np.array([[0.1, 0.4, 0.9], [-1.0, 0.6, 0.5]])
+    G = np.array([[0.0, 1.0], [-1.0, 0.5]])
+    om = np.array([1.0, 2.0, 3.0])
+    np.testing.assert_allclose(orc.eq5_objective(w, om, G), [0.36, 0.02], rtol=1e-12)
+    # one row alone, and a weight exactly on a midpoint (either neighbour: same distance)
+    np.testing.assert_allclose(orc.eq5_objective(w[0], om, G[0]), 0.36, rtol=1e-12)
+    np.testing.assert_allclose(orc.eq5_objective(np.array([0.5]), np.array([7.0]), np.array([0.0, 1.0])), 1.75, rtol=1e-12)
+
+
+def test_eq7_objective_hand_computed():
+    """Eq. 7 by hand at b = 2 with S = 0.5, Z = 1, i.e. the grid (code - Z) S = (-0.5, 0, 0.5, 1):
+    w = 0.3: round(0.6) + 1 = 2 -> 0.5, error 0.2;  w = -0.9: round(-1.8) + 1 = -1 -> clipped to
+    0 -> -0.5, error 0.4;  w = 1.4: round(2.8) + 1 = 4 -> clipped to 3 -> 1.0, error 0.4;
+    omega = (2, 1, 4) -> 2 * 0.04 + 1 * 0.16 + 4 * 0.16 = 0.88 (0.36 without omega; 0.24 without
+    the clipping, whose grid would reach -1 and 1.5)."""
+    w = np.array([0.3, -0.9, 1.4])
+    om = np.array([2.0, 1.0, 4.0])
+    assert orc.eq7_objective(w, om, 0.5, 1.0, 2) == pytest.approx(0.88, rel=1e-12)
+    # a grid that contains every weight scores zero; scaling omega scales the objective
+    assert orc.eq7_objective(np.array([-0.5, 0.0, 1.0]), om, 0.5, 1.0, 2) == 0.0
+    assert orc.eq7_objective(w, 3.0 * om, 0.5, 1.0, 2) == pytest.approx(2.64, rel=1e-12)
+
+
 def test_t0_is_minmax_grid():
     """No shrinkage (t = 0) leaves the min-max S and Z of Section 2.1."""
     g = RNG(12)
