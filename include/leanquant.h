@@ -18,9 +18,10 @@
  *
  * Conventions shared by all calls
  *   - Every pointer is a DEVICE pointer unless the comment says "host".  The
- *     caller owns every buffer; the library allocates no device memory and
- *     keeps no state between calls apart from a thread-local error string and
- *     the side stream mentioned below.
+ *     caller owns every buffer; the library allocates no device memory.  State
+ *     kept between calls: a thread-local error string, the side streams mentioned
+ *     below, per-device "kernel attributes are set" flags (set once under a mutex),
+ *     and the built-in scratch array of lq_fit_grid_static with its per-device address.
  *   - All matrices are row-major fp32 with an explicit leading dimension
  *     counted in elements.  W is r x c with rows = output channels and
  *     columns = input channels, as in the paper (W in R^{r x c}).
@@ -167,6 +168,23 @@ lq_status lq_fit_grid(const float* W, int64_t r, int64_t c, int64_t ldw, const f
 lq_status lq_fit_grid_from(const float* W, int64_t r, int64_t c, int64_t ldw, const float* hinv_diag,
                            const lq_params* P, const float* init_grid, float* grid, void* ws,
                            size_t ws_bytes, void* stream);
+
+/*
+ * lq_fit_grid for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and
+ * results as lq_fit_grid (bit-identical: the same kernels run), but the scratch (the importance
+ * weights of the c columns, 12 bytes per column) lives in a 192 KiB array inside the library's
+ * device image, one copy per GPU for the life of the process.  The call allocates nothing
+ * (no hipMalloc / hipFree, no allocating library routine); the first call on a device looks up
+ * the array's device address (with that device current) and keeps it.
+ *   Limit: c <= 16384 (LQ_ERR_UNSUPPORTED beyond; use lq_fit_grid with a workspace).
+ *   The array keeps the previous call's contents; every entry read is written first by the
+ *   same call, so nothing is cleared.  All calls on one GPU share the array: two calls whose
+ *   work overlaps on that GPU (different streams, or different host threads) race on it --
+ *   order them on one stream or with events.
+ */
+lq_status lq_fit_grid_static(const float* W, int64_t r, int64_t c, int64_t ldw, const float* hinv_diag,
+                             const lq_params* P, float* grid, void* stream);
 
 /*
  * Weighted k-means++ seeding of the non-uniform grids: the initialisation that the paper's

@@ -23,7 +23,7 @@ LQ_CALL_HESSIAN, LQ_CALL_CHOLESKY, LQ_CALL_FIT_GRID, LQ_CALL_QUANTIZE, LQ_CALL_E
 
 EXPORTS = ("lq_params_default", "lq_hessian_accumulate", "lq_hessian_accumulate_host",
            "lq_hessian_host_workspace_bytes", "lq_cholesky_inv", "lq_fit_grid",
-           "lq_fit_grid_from", "lq_kmeanspp_seed", "lq_quantize_layer", "lq_quantize_exact", "lq_hinv_from_factor", "lq_packed_row_bytes", "lq_bits_per_weight", "lq_pack_layer",
+           "lq_fit_grid_static", "lq_fit_grid_from", "lq_kmeanspp_seed", "lq_quantize_layer", "lq_quantize_exact", "lq_hinv_from_factor", "lq_packed_row_bytes", "lq_bits_per_weight", "lq_pack_layer",
            "lq_unpack_layer", "lq_matvec_packed", "lq_workspace_bytes", "lq_last_error", "lq_version")
 
 
@@ -66,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.lq_cholesky_inv.restype = ctypes.c_int
     lib.lq_fit_grid.argtypes = [vp, i64, i64, i64, vp, pp, vp, vp, sz, vp]
     lib.lq_fit_grid.restype = ctypes.c_int
+    lib.lq_fit_grid_static.argtypes = [vp, i64, i64, i64, vp, pp, vp, vp]
+    lib.lq_fit_grid_static.restype = ctypes.c_int
     lib.lq_fit_grid_from.argtypes = [vp, i64, i64, i64, vp, pp, vp, vp, vp, sz, vp]
     lib.lq_fit_grid_from.restype = ctypes.c_int
     lib.lq_kmeanspp_seed.argtypes = [vp, i64, i64, i64, vp, pp, vp, vp, vp, sz, vp]
@@ -224,13 +226,25 @@ def lq_fit_grid(W: torch.Tensor, hinv_diag: torch.Tensor, P: lq_params, grid: to
                               _ptr(grid, torch.float32, "grid"), wp, wn, _stream()))
 
 
+def lq_fit_grid_static(W: torch.Tensor, hinv_diag: torch.Tensor, P: lq_params, grid: torch.Tensor) -> None:
+    """lq_fit_grid without a workspace argument (the library's built-in scratch, c <= 16384)."""
+    r, c = W.shape
+    _dense(hinv_diag, (c,), "hinv_diag")
+    _dense(grid, grid_shape(P, r, c), "grid")
+    _check(load().lq_fit_grid_static(_ptr(W, torch.float32, "W"), r, c, _ld(W, "W"),
+                                     _ptr(hinv_diag, torch.float32, "hinv_diag"), ctypes.byref(P),
+                                     _ptr(grid, torch.float32, "grid"), _stream()))
+
+
 def lq_fit_grid_from(W: torch.Tensor, hinv_diag: torch.Tensor, P: lq_params,
                      init_grid: Optional[torch.Tensor], grid: torch.Tensor, ws: torch.Tensor) -> None:
     r, c = W.shape
     wp, wn = _ws(ws)
     _dense(hinv_diag, (c,), "hinv_diag")
     _dense(grid, grid_shape(P, r, c), "grid")
-    _dense(init_grid, grid_shape(P, r, c), "init_grid")
+    if init_grid is not None:
+        # (with an affine P the C side refuses a starting grid; only a view is refused here)
+        _dense(init_grid, (r, 1 << P.bits) if P.mode == LQ_GRID_NONUNIFORM else tuple(init_grid.shape), "init_grid")
     _check(load().lq_fit_grid_from(_ptr(W, torch.float32, "W"), r, c, _ld(W, "W"),
                                    _ptr(hinv_diag, torch.float32, "hinv_diag"), ctypes.byref(P),
                                    _ptr(init_grid, torch.float32, "init_grid"),

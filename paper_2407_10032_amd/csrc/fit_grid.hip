@@ -389,12 +389,55 @@ namespace {
 lq_status fit_grid_impl(const float* W, int64_t r, int64_t c, int64_t ldw, const float* hinv_diag,
                         const lq_params* P, const float* init_grid, float* grid, void* ws,
                         size_t ws_bytes, void* stream);
+
+// ---- scratch of lq_fit_grid_static: the importance weights of up to STATIC_MAX_C columns in
+// fp64 and fp32, held in the library's own device image (one copy per GPU, for the life of the
+// process).  Host code never uses the array's name as an address: its device address is asked
+// for once per device and kept.
+constexpr int64_t STATIC_MAX_C = 16384;
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)STATIC_MAX_C * (sizeof(double) + sizeof(float));
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+lq_status static_scratch(void** out) {
+  static std::mutex mu;
+  static void* ptr[lq::MAX_DEVICES] = {};
+  int dev = -1;
+  LQ_CHECK_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= lq::MAX_DEVICES)
+    return lq::fail(LQ_ERR_UNSUPPORTED, "lq_fit_grid_static: device index %d (limit %d)", dev, lq::MAX_DEVICES);
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    LQ_CHECK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return lq::fail(LQ_ERR_HIP, "lq_fit_grid_static: the scratch array has no device address");
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return LQ_OK;
 }
+}
+
 
 extern "C" lq_status lq_fit_grid(const float* W, int64_t r, int64_t c, int64_t ldw,
                                  const float* hinv_diag, const lq_params* P, float* grid, void* ws,
                                  size_t ws_bytes, void* stream) {
   return fit_grid_impl(W, r, c, ldw, hinv_diag, P, nullptr, grid, ws, ws_bytes, stream);
+}
+
+extern "C" lq_status lq_fit_grid_static(const float* W, int64_t r, int64_t c, int64_t ldw,
+                                        const float* hinv_diag, const lq_params* P, float* grid,
+                                        void* stream) {
+  if (c > STATIC_MAX_C)
+    return lq::fail(LQ_ERR_UNSUPPORTED, "lq_fit_grid_static: c=%lld exceeds the built-in scratch (c <= %lld); "
+                    "use lq_fit_grid with a workspace", (long long)c, (long long)STATIC_MAX_C);
+  if (c >= 1 && lq::fit_grid_workspace_bytes(c) > STATIC_SCRATCH_BYTES)
+    return lq::fail(LQ_ERR_UNSUPPORTED, "lq_fit_grid_static: c=%lld needs more than the built-in scratch", (long long)c);
+  void* ws = nullptr;
+  lq_status st = static_scratch(&ws);
+  if (st != LQ_OK) return st;
+  // the kernels write every scratch entry they later read (importance weights of the c
+  // columns), so nothing needs clearing between calls
+  return fit_grid_impl(W, r, c, ldw, hinv_diag, P, nullptr, grid, ws, STATIC_SCRATCH_BYTES, stream);
 }
 
 extern "C" lq_status lq_fit_grid_from(const float* W, int64_t r, int64_t c, int64_t ldw,
