@@ -173,7 +173,7 @@ lq_status lq_fit_grid_from(const float* W, int64_t r, int64_t c, int64_t ldw, co
  * lq_fit_grid for callers that cannot allocate device memory or pass a workspace: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and
  * results as lq_fit_grid (bit-identical: the same kernels run), but the scratch (the importance
- * weights of the c columns, 12 bytes per column) lives in a 192 KiB array inside the library's
+ * weights of the c columns, 12 bytes per column, and a row counter) lives in a 192 KiB array inside the library's
  * device image, one copy per GPU for the life of the process.  The call allocates nothing
  * (no hipMalloc / hipFree, no allocating library routine); the first call on a device looks up
  * the array's device address (with that device current) and keeps it.

@@ -1,9 +1,10 @@
 // lq_fit_grid: loss-error-aware grids (Algorithm 1 lines 5-9).
 //
-// Non-uniform (Eq. 5, init Eq. 6): one workgroup walks rows of W; a row's weights
-// and the importance weights live in registers (one HBM read of W), every Lloyd
-// iteration is compare-and-accumulate in registers/LDS, and the 2*2^b cluster sums
-// are reduced in a fixed order (double precision across threads).
+// Non-uniform (Eq. 5, init Eq. 6): workgroups take rows of W from a counter; a row's weights
+// and importance weights live in registers (one HBM read of W), a weight's cluster comes
+// from a table over fine bins of the row's range (one table byte, one midpoint, one compare
+// instead of 2^b - 1 compares), and the 2 * 2^b cluster sums are reduced in a fixed order
+// (double precision across threads).
 //
 // Affine (Eq. 7, t from Eq. 8): the candidate set {(t_min, t_max)} collapses to far
 // fewer distinct grids.  S depends only on s = t_min + t_max, and for a fixed s the
@@ -29,8 +30,10 @@ constexpr int NT = 256;  // threads per workgroup
 // keeps the values inside fp32 range).
 __global__ __launch_bounds__(1024) void importance_kernel(const float* __restrict__ d, int64_t c,
                                                           float p, float* __restrict__ om32,
-                                                          double* __restrict__ om64) {
+                                                          double* __restrict__ om64,
+                                                          int* __restrict__ next_row) {
   __shared__ float red[1024];
+  if (threadIdx.x == 0) *next_row = 0;      // row counter of the non-uniform fit
   float m = INFINITY;
   for (int64_t i = threadIdx.x; i < c; i += 1024) m = fminf(m, d[i]);
   red[threadIdx.x] = m;
@@ -59,20 +62,66 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ------------------------------------------------------------ non-uniform: weighted Lloyd
-template <int K, int EPT>
-__global__ __launch_bounds__(NT) void kmeans_rows_kernel(const float* __restrict__ W, int64_t r,
+// Workgroups take rows from a shared counter (rows need from 2 to 100 Lloyd updates, so a
+// fixed split would leave compute units idle).  A row's weights, their importance weights
+// and the fine bin each weight falls into stay in registers (W is read from HBM exactly once).
+//
+// Cluster of a weight = number of midpoints of the current grid below it.  Instead of
+// comparing every weight with all 2^b - 1 midpoints in every iteration, the range
+// [min, max] of the row is cut into NBIN equal bins once; in an iteration a table over the
+// bins holds c0 = how many midpoints lie in lower bins.  The bin function is monotone, so a
+// midpoint in a lower bin is below the weight and one in a higher bin is above it: only the
+// midpoints that share the weight's bin need a comparison, and they are midpoints c0,
+// c0 + 1, ...  With at most one midpoint per bin (the usual case) a weight costs one table
+// byte, one midpoint and one compare; if some bin holds n > 1 of them (a grid much finer
+// than the bins) every weight compares with n consecutive midpoints -- those beyond its
+// bin lie above it and add nothing -- so the count is the same in every case.
+//
+// Sums: each thread adds omega * w and omega to its own slot of the cluster (cluster-major,
+// so a wavefront's slots never share an LDS bank whatever the clusters are; the slots of the
+// next weight are read before those of the current one are written, with the fresh values
+// carried over when both hit the same slot); the 2 * 2^b columns are then added in a fixed
+// order in double and the lanes that hold a cluster's two sums form its new grid point.
+// Lloyd stops when no grid point changes.
+constexpr int NBIN = 1024;
+
+__device__ __forceinline__ double recip_f64(double x) {
+  // reciprocal to ~1e-30 relative: hardware estimate and two Newton steps (the quotient is
+  // rounded to fp32 afterwards)
+  double y = __builtin_amdgcn_rcp(x);
+  y = fma(fma(-x, y, 1.0), y, y);
+  y = fma(fma(-x, y, 1.0), y, y);
+  return y;
+}
+
+// NTK threads per workgroup (256, or 512 for long rows so that a thread holds at most 32
+// weights); the second launch bound is the number of wavefronts per SIMD the register
+// allocation must leave room for.
+template <int K, int EPT, int NTK>
+__global__ __launch_bounds__(NTK, 4) void kmeans_rows_kernel(const float* __restrict__ W, int64_t r,
                                                          int64_t c, int64_t ldw,
                                                          const float* __restrict__ om32,
                                                          const float* __restrict__ init,
-                                                         int max_iter, float* __restrict__ G) {
-  constexpr int ACC_LD = 2 * K + 1;
-  constexpr int PARTS = NT / (2 * K);   // threads that share one column of the reduction
-  constexpr int RPP = NT / PARTS;       // accumulator rows per part (= 2K)
-  __shared__ float sAcc[NT * ACC_LD];
-  __shared__ double sSum[2 * K];
+                                                         int max_iter, float* __restrict__ G,
+                                                         int* __restrict__ next_row) {
+  constexpr int NT = NTK;               // (shadows the file-level constant on purpose)
+  constexpr int NW = NT / 64;
+  constexpr int PARTS = (NT / (2 * K) < 32) ? NT / (2 * K) : 32;   // threads per column of the reduction
+  constexpr int RPP = NT / PARTS;       // slots each of them adds (a power of two)
+  constexpr int BPT = NBIN / NT;        // bins per thread when the table is built
+  static_assert(2 * PARTS <= 64 && RPP % 4 == 0 && (2 * K * PARTS) % 64 == 0 && 2 * K * PARTS <= NT,
+                "a cluster's two columns sit in one wavefront; whole wavefronts take part");
+  static_assert(BPT == 4 || BPT == 2, "table build handles 2 or 4 bins per thread");
+  __shared__ __align__(16) float sAcc[2 * K * NT];   // [2K][NT]: sums of omega w, then of omega
+  __shared__ __align__(16) uint8_t sLut[NBIN];       // c0 of every bin
+  __shared__ __align__(16) int sCnt[NBIN];           // midpoints per bin
+  __shared__ __align__(16) int sBm[16];              // bin of midpoint m (NBIN beyond K - 1)
   __shared__ float sG[K];
-  __shared__ float sRed[8];
-  __shared__ int sChanged[2];
+  __shared__ float sMid[2 * K];                      // midpoints, +inf beyond K - 1
+  __shared__ float sRed[2 * NW];
+  __shared__ int sChanged[2];                        // by iteration parity
+  __shared__ int sMulti;                             // most midpoints in one bin
+  __shared__ int sRow;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
@@ -82,76 +131,198 @@ __global__ __launch_bounds__(NT) void kmeans_rows_kernel(const float* __restrict
     int64_t col = (int64_t)e * NT + tid;
     om[e] = (col < c) ? om32[col] : 0.0f;
   }
+  for (int i = tid; i < NBIN; i += NT) sCnt[i] = 0;
+  if (tid < 16) sBm[tid] = NBIN;
+  if (tid < 2 * K) sMid[tid] = INFINITY;
+  int bm_mine = 0;      // wavefront 0, lane m: bin of midpoint m of the grid last published
 
-  for (int64_t row = blockIdx.x; row < r; row += gridDim.x) {
+  for (;;) {
+    if (tid == 0) sRow = atomicAdd(next_row, 1);
+    __syncthreads();
+    const int64_t row = sRow;
+    if (row >= r) break;
     float w[EPT];
     float lo = INFINITY, hi = -INFINITY;
+    {
+      // 32-bit column offsets from the row's (uniform) base; the opaque copy of the thread
+      // index keeps the compiler from holding an address and a predicate per weight in
+      // registers across rows
+      const float* wrow = W + row * ldw;
+      uint32_t t0 = (uint32_t)tid;
+      asm volatile("" : "+v"(t0));
+      const uint32_t cc = (uint32_t)c;
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      int64_t col = (int64_t)e * NT + tid;
-      if (col < c) {
-        w[e] = W[row * ldw + col];
-        lo = fminf(lo, w[e]);
-        hi = fmaxf(hi, w[e]);
-      } else {
-        w[e] = 0.0f;
+      for (int e = 0; e < EPT; ++e) {
+        const uint32_t col = (uint32_t)(e * NT) + t0;
+        if (col < cc) {
+          w[e] = wrow[col];
+          lo = fminf(lo, w[e]);
+          hi = fmaxf(hi, w[e]);
+        } else {
+          w[e] = 0.0f;
+        }
       }
     }
     lo = wave_min(lo);
     hi = wave_max(hi);
-    if (lane == 0) { sRed[wave] = lo; sRed[4 + wave] = hi; }
-    if (tid == 0) { sChanged[0] = 0; sChanged[1] = 0; }
+    if (lane == 0) { sRed[wave] = lo; sRed[NW + wave] = hi; }
     __syncthreads();
-    lo = fminf(fminf(sRed[0], sRed[1]), fminf(sRed[2], sRed[3]));
-    hi = fmaxf(fmaxf(sRed[4], sRed[5]), fmaxf(sRed[6], sRed[7]));
-    // Eq. 6: evenly spaced initial grid from min to max, unless the caller supplies one
-    if (tid < K) sG[tid] = init ? init[row * K + tid] : lo + (hi - lo) / (float)(K - 1) * (float)tid;
+    lo = sRed[0];
+    hi = sRed[NW];
+#pragma unroll
+    for (int v = 1; v < NW; ++v) { lo = fminf(lo, sRed[v]); hi = fmaxf(hi, sRed[NW + v]); }
+    // monotone bin function of this row (a constant row puts everything into bin 0)
+    const float bscale = (hi > lo) ? (float)NBIN / (hi - lo) : 0.0f;
+    auto bin_of = [&](float x) -> int {
+      return (int)fminf(fmaxf((x - lo) * bscale, 0.0f), (float)(NBIN - 1));
+    };
+    // the weights' bins, two 16-bit values per register; with 32 weights per thread they are
+    // recomputed in every iteration instead (registers)
+    constexpr bool KEEP_BINS = EPT <= 22;
+    uint32_t ba2[KEEP_BINS ? (EPT + 1) / 2 : 1];
+    if constexpr (KEEP_BINS) {
+#pragma unroll
+      for (int e = 0; e < EPT; e += 2) {
+        const uint32_t b0 = (uint32_t)bin_of(w[e]);
+        const uint32_t b1 = (e + 1 < EPT) ? (uint32_t)bin_of(w[e + 1]) : 0u;
+        ba2[e >> 1] = b0 | (b1 << 16);
+      }
+    }
+
+    // Wavefront 0 publishes a grid that lanes 0..K-1 have written to sG: its midpoints,
+    // their bins, and the number of midpoints per bin.
+    auto publish = [&]() {
+      __builtin_amdgcn_wave_barrier();
+      if (tid < K - 1) {
+        const float m = 0.5f * (sG[tid] + sG[tid + 1]);
+        const int b = bin_of(m);
+        sMid[tid] = m;
+        sBm[tid] = b;
+        atomicAdd(&sCnt[b], 1);
+        bm_mine = b;
+      }
+      if (tid == 0) sMulti = 0;
+    };
+    if (wave == 0) {
+      if (tid < K - 1) sCnt[bm_mine] = 0;      // counts left by the previous row's last grid
+      // Eq. 6: evenly spaced initial grid from min to max, unless the caller supplies one
+      if (tid < K) sG[tid] = init ? init[row * K + tid] : lo + (hi - lo) / (float)(K - 1) * (float)tid;
+      if (tid == 0) { sChanged[0] = 0; sChanged[1] = 0; }
+      publish();
+    }
     __syncthreads();
 
     for (int it = 0; it < max_iter; ++it) {
-      float mid[K - 1];
+      // ---- table over the bins for the published grid (4 consecutive bins per thread)
+      {
+        const int b0 = BPT * tid;
+        int c0 = 0;
 #pragma unroll
-      for (int m = 0; m < K - 1; ++m) mid[m] = 0.5f * (sG[m] + sG[m + 1]);
-      float* mine = sAcc + tid * ACC_LD;
+        for (int m = 0; m < K - 1; ++m) c0 += (sBm[m] < b0) ? 1 : 0;
+        int nmax;
+        if constexpr (BPT == 4) {
+          const int4 n4 = *reinterpret_cast<const int4*>(&sCnt[b0]);
+          const int c1 = c0 + n4.x, c2 = c1 + n4.y, c3 = c2 + n4.z;
+          reinterpret_cast<uint32_t*>(sLut)[tid] =
+              (uint32_t)c0 | ((uint32_t)c1 << 8) | ((uint32_t)c2 << 16) | ((uint32_t)c3 << 24);
+          nmax = max(max(n4.x, n4.y), max(n4.z, n4.w));
+        } else {
+          const int2 n2 = *reinterpret_cast<const int2*>(&sCnt[b0]);
+          reinterpret_cast<uint16_t*>(sLut)[tid] = (uint16_t)((uint32_t)c0 | ((uint32_t)(c0 + n2.x) << 8));
+          nmax = max(n2.x, n2.y);
+        }
+        if (nmax >= 2) atomicMax(&sMulti, nmax);
+        // the private sums start from zero (cleared cooperatively, 16 bytes per store)
+        float4* z = reinterpret_cast<float4*>(sAcc);
 #pragma unroll
-      for (int m = 0; m < 2 * K; ++m) mine[m] = 0.0f;
-      // Columns past c hold w = 0 with omega = 0 and add nothing.  The cluster of a weight is
-      // the number of midpoints below it, counted from the sign bits of mid - w (w > mid
-      // exactly when the difference is negative): no comparison masks, no selects, no
-      // branches, so the loop is one block and the LDS updates of one weight overlap the
-      // counting of the next.  (Measured alternatives: a bisection over the midpoints, same
-      // speed; the read-add-writes of four weights batched, 8 % slower; LDS float atomics on
-      // the thread's own slots, five times slower.)
-#pragma unroll
-      for (int e = 0; e < EPT; ++e) {
-        uint32_t cnt = 0;
-#pragma unroll
-        for (int m = 0; m < K - 1; ++m) cnt += __float_as_uint(mid[m] - w[e]) >> 31;
-        mine[cnt] += om[e] * w[e];
-        mine[K + cnt] += om[e];
+        for (int q = 0; q < 2 * K / 4; ++q) z[q * NT + tid] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (tid == 0) sChanged[(it + 1) & 1] = 0;
       }
+      __syncthreads();
+      const int multi = sMulti;
+      // ---- every weight into its cluster's sums.  Columns past c hold w = 0, omega = 0.
+      auto accumulate = [&](auto multi_tag) {
+        constexpr bool MULTI = decltype(multi_tag)::value;
+        auto cluster_of = [&](int e) -> int {
+          uint32_t b;
+          if constexpr (KEEP_BINS) b = (e & 1) ? (ba2[e >> 1] >> 16) : (ba2[e >> 1] & 0xffffu);
+          else b = (uint32_t)bin_of(w[e]);
+          const int c0 = sLut[b];
+          if (!MULTI) return c0 + ((w[e] > sMid[c0]) ? 1 : 0);
+          int k2 = c0;
+          for (int k = 0; k < multi; ++k) k2 += (w[e] > sMid[c0 + k]) ? 1 : 0;
+          return k2;
+        };
+        int cl = cluster_of(0);
+        float* p = sAcc + cl * NT + tid;
+        float a = p[0], b = p[K * NT];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+          int cn = cl;
+          float* pn = p;
+          float an = 0.f, bn = 0.f;
+          if (e + 1 < EPT) {
+            cn = cluster_of(e + 1);
+            pn = sAcc + cn * NT + tid;
+            an = pn[0];
+            bn = pn[K * NT];
+          }
+          a = fmaf(om[e], w[e], a);
+          b += om[e];
+          p[0] = a;
+          p[K * NT] = b;
+          if (e + 1 < EPT) {
+            const bool same = cn == cl;
+            a = same ? a : an;
+            b = same ? b : bn;
+            p = pn;
+            cl = cn;
+          }
+          // keep the compiler from hoisting the table reads of many weights ahead (registers)
+          if ((e & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+      };
+      if (multi <= 1) accumulate(std::false_type{});
+      else accumulate(std::true_type{});
       __syncthreads();
       {
-        // column sums of the NT x 2K accumulator array, fixed order, in double
-        const int colm = tid / PARTS, part = tid % PARTS;
-        double s = 0.0;
-        for (int q = 0; q < RPP; ++q) s += (double)sAcc[(part * RPP + q) * ACC_LD + colm];
+        // Column sums of the 2K x NT slots in double.  Thread group gidx = 2 m + which adds
+        // column which * K + m (which = 0: sum of omega w, 1: sum of omega of cluster m); a
+        // thread adds RPP slots starting at a lane-dependent one so that a wavefront reads
+        // distinct banks.  The two groups of a cluster are PARTS lanes apart.
+        const int gidx = tid / PARTS, part = tid % PARTS;
+        const int m = (gidx >> 1) & (K - 1), which = gidx & 1;      // groups beyond 2K idle along
+        const float* src = sAcc + (which * K + m) * NT + part * RPP;
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll 2
+        for (int q = 0; q < RPP; q += 4) {
+          s0 += (double)src[(q + tid) & (RPP - 1)];
+          s1 += (double)src[(q + 1 + tid) & (RPP - 1)];
+          s2 += (double)src[(q + 2 + tid) & (RPP - 1)];
+          s3 += (double)src[(q + 3 + tid) & (RPP - 1)];
+        }
+        double s = (s0 + s1) + (s2 + s3);
 #pragma unroll
         for (int o = PARTS / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-        if (part == 0) sSum[colm] = s;
-      }
-      __syncthreads();
-      if (tid < K) {
-        double den = sSum[K + tid];
-        float old = sG[tid];
-        float gn = (den > 0.0) ? (float)(sSum[tid] / den) : old;
-        if (gn != old) sChanged[it & 1] = 1;
-        sG[tid] = gn;
+        const double den = __shfl_down(s, PARTS, 64);
+        if (which == 0 && part == 0 && gidx < 2 * K) {
+          const float old = sG[m];
+          // an empty cluster keeps its point
+          const float gn = (den > 0.0) ? (float)(s * recip_f64(den)) : old;
+          if (gn != old) {
+            sG[m] = gn;
+            sChanged[it & 1] = 1;
+          }
+        }
       }
       __syncthreads();
       const int changed = sChanged[it & 1];
-      if (tid == 0) sChanged[(it + 1) & 1] = 0;
+      if (wave == 0) {
+        if (tid < K - 1) sCnt[bm_mine] = 0;                  // counts of the grid just used
+        if (changed) publish();
+      }
       if (!changed) break;
+      __syncthreads();
     }
     if (tid < K) G[row * K + tid] = sG[tid];
     __syncthreads();
@@ -359,19 +530,21 @@ __global__ __launch_bounds__(NTA) void affine_search_kernel(const float* __restr
 
 template <int K>
 lq_status launch_kmeans(const float* W, int64_t r, int64_t c, int64_t ldw, const float* om32,
-                        const float* init, int max_iter, float* G, hipStream_t st) {
-  int64_t ept = lq::ceil_div(c, NT);
-  unsigned grid = (unsigned)(r < 2048 ? r : 2048);
-#define LQ_KM(E)                                                                              \
-  hipLaunchKernelGGL((kmeans_rows_kernel<K, E>), dim3(grid), dim3(NT), 0, st, W, r, c, ldw, \
-                     om32, init, max_iter, G)
-  if (ept <= 2) LQ_KM(2);
-  else if (ept <= 4) LQ_KM(4);
-  else if (ept <= 8) LQ_KM(8);
-  else if (ept <= 16) LQ_KM(16);
-  else if (ept <= 32) LQ_KM(32);
-  else if (ept <= 44) LQ_KM(44);
-  else LQ_KM(64);
+                        const float* init, int max_iter, float* G, int* next_row, hipStream_t st) {
+  // rows are handed out by a counter, so the grid only has to cover the workgroups that
+  // can be resident (at most 4 per compute unit)
+  unsigned grid = (unsigned)(r < 1024 ? r : 1024);
+#define LQ_KM(E, T)                                                                              \
+  hipLaunchKernelGGL((kmeans_rows_kernel<K, E, T>), dim3(grid), dim3(T), 0, st, W, r, c, ldw,   \
+                     om32, init, max_iter, G, next_row)
+  // a thread holds E weights of the row: 256 threads up to 4096 columns, 512 beyond
+  if (c <= 2 * 256) LQ_KM(2, 256);
+  else if (c <= 4 * 256) LQ_KM(4, 256);
+  else if (c <= 8 * 256) LQ_KM(8, 256);
+  else if (c <= 16 * 256) LQ_KM(16, 256);
+  else if (c <= 16 * 512) LQ_KM(16, 512);
+  else if (c <= 22 * 512) LQ_KM(22, 512);
+  else LQ_KM(32, 512);
 #undef LQ_KM
   LQ_CHECK_LAUNCH("kmeans_rows_kernel");
   return LQ_OK;
@@ -381,7 +554,8 @@ lq_status launch_kmeans(const float* W, int64_t r, int64_t c, int64_t ldw, const
 
 namespace lq {
 size_t fit_grid_workspace_bytes(int64_t c) {
-  return align_up((size_t)c * sizeof(double), 256) + align_up((size_t)c * sizeof(float), 256);
+  // importance weights in fp64 and fp32, and the row counter of the non-uniform fit
+  return align_up((size_t)c * sizeof(double), 256) + align_up((size_t)c * sizeof(float), 256) + 256;
 }
 }  // namespace lq
 
@@ -395,7 +569,7 @@ lq_status fit_grid_impl(const float* W, int64_t r, int64_t c, int64_t ldw, const
 // process).  Host code never uses the array's name as an address: its device address is asked
 // for once per device and kept.
 constexpr int64_t STATIC_MAX_C = 16384;
-constexpr size_t STATIC_SCRATCH_BYTES = (size_t)STATIC_MAX_C * (sizeof(double) + sizeof(float));
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)STATIC_MAX_C * (sizeof(double) + sizeof(float)) + 256;
 static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 
 lq_status static_scratch(void** out) {
@@ -416,7 +590,6 @@ lq_status static_scratch(void** out) {
   return LQ_OK;
 }
 }
-
 
 extern "C" lq_status lq_fit_grid(const float* W, int64_t r, int64_t c, int64_t ldw,
                                  const float* hinv_diag, const lq_params* P, float* grid, void* ws,
@@ -466,15 +639,16 @@ lq_status fit_grid_impl(const float* W, int64_t r, int64_t c, int64_t ldw, const
   hipStream_t st = (hipStream_t)stream;
   double* om64 = (double*)ws;
   float* om32 = (float*)((char*)ws + lq::align_up((size_t)c * sizeof(double), 256));
+  int* next_row = (int*)((char*)om32 + lq::align_up((size_t)c * sizeof(float), 256));
 
   if (P->mode == LQ_GRID_NONUNIFORM) {
-    if (c > 64 * NT) return lq::fail(LQ_ERR_UNSUPPORTED, "lq_fit_grid: non-uniform fit supports c <= %d", 64 * NT);
-    hipLaunchKernelGGL(importance_kernel, dim3(1), dim3(1024), 0, st, hinv_diag, c, P->p, om32, om64);
+    if (c > 32 * 512) return lq::fail(LQ_ERR_UNSUPPORTED, "lq_fit_grid: non-uniform fit supports c <= %d", 32 * 512);
+    hipLaunchKernelGGL(importance_kernel, dim3(1), dim3(1024), 0, st, hinv_diag, c, P->p, om32, om64, next_row);
     LQ_CHECK_LAUNCH("importance_kernel");
     switch (P->bits) {
-      case 2: return launch_kmeans<4>(W, r, c, ldw, om32, init_grid, P->kmeans_max_iter, grid, st);
-      case 3: return launch_kmeans<8>(W, r, c, ldw, om32, init_grid, P->kmeans_max_iter, grid, st);
-      default: return launch_kmeans<16>(W, r, c, ldw, om32, init_grid, P->kmeans_max_iter, grid, st);
+      case 2: return launch_kmeans<4>(W, r, c, ldw, om32, init_grid, P->kmeans_max_iter, grid, next_row, st);
+      case 3: return launch_kmeans<8>(W, r, c, ldw, om32, init_grid, P->kmeans_max_iter, grid, next_row, st);
+      default: return launch_kmeans<16>(W, r, c, ldw, om32, init_grid, P->kmeans_max_iter, grid, next_row, st);
     }
   }
 
@@ -482,7 +656,7 @@ lq_status fit_grid_impl(const float* W, int64_t r, int64_t c, int64_t ldw, const
   if (g > 8192) return lq::fail(LQ_ERR_UNSUPPORTED, "lq_fit_grid: affine group of %lld columns (limit 8192)", (long long)g);
   const int64_t ngroups = c / g;
   if (r * ngroups > 0x7fffffffLL) return lq::fail(LQ_ERR_UNSUPPORTED, "lq_fit_grid: more than 2^31 groups");
-  hipLaunchKernelGGL(importance_kernel, dim3(1), dim3(1024), 0, st, hinv_diag, c, P->p, om32, om64);
+  hipLaunchKernelGGL(importance_kernel, dim3(1), dim3(1024), 0, st, hinv_diag, c, P->p, om32, om64, next_row);
   LQ_CHECK_LAUNCH("importance_kernel");
   const size_t lds = (size_t)g * 2 * sizeof(double);
   const int t = lq::resolve_t(P);

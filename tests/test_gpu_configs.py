@@ -130,6 +130,56 @@ def test_config3_shape_nonuniform_3bit():
     assert (1.0 - gok) * rows.size <= 1.0 + 1e-9 and agree >= 0.999 and abs(lr - 1.0) < 1e-3
 
 
+def test_config3_shape_with_few_tokens():
+    """The c3 layer with 16384 tokens, N ~ 1.5 c: H is poorly conditioned, the rows of U are dense,
+    and one decision taken the other way changes about a tenth of the row's later codes (they all
+    feel the changed error through lines 16-19 of Algorithm 1), i.e. 0.1 % of a 96-row sample.
+    fp32 and float64 legitimately part ways where a weight sits within rounding noise of the
+    midpoint of two grid points, so here a row must either carry the oracle's codes or FIRST
+    differ at such a near-tie: adjacent codes, and the oracle's own working weight within 1e-3
+    of a grid step of the midpoint (a wrong decision would sit anywhere in the half step, so
+    it passes this with probability 2e-3).  Such a row is a valid trajectory with another
+    loss: its loss must stay within 5 % of the oracle's, the layer's within 1e-3, and the
+    pooled code agreement above 99.5 % (at most a few such rows in 96)."""
+    cfg = lq_synth.CONFIGS["c3"].scaled(n_tokens=16384)
+    P = hx.params_for(cfg)
+    _say("c3 (c = 11008, 3-bit non-uniform), 16384 tokens (N ~ 1.5 c)")
+    Hg, Ug, dg, grid, Wq, codes, row_loss = _device_layer(cfg, P)
+    H = _oracle_hessian(cfg)
+    U, d = orc.cholesky_inv(H, cfg.damp)
+    _check_hud(Hg.cpu().numpy(), Ug.cpu().numpy(), dg.cpu().numpy(), H, U, d, cfg.n_tokens)
+    rows = lq_synth.sample_rows(cfg, 96)
+    W_rows = lq_synth.weights(cfg, rows)
+    G = orc.fit_grid_nu(W_rows, d, cfg.bits, cfg.p)
+    What, codes_ref, loss_ref = orc.quantize_layer(W_rows, U, G, "nu", cfg.bits, B=cfg.block)
+    Gg = grid.cpu().numpy()[rows]
+    cg = codes.cpu().numpy()[rows].astype(np.int64)
+    assert hx.nu_grid_match(Gg, G).all()
+    differs = np.nonzero((cg != codes_ref).any(axis=1))[0]
+    rl = row_loss.cpu().numpy()[rows]
+    for k in differs:
+        j = int(np.nonzero(cg[k] != codes_ref[k])[0][0])
+        a, b = int(codes_ref[k, j]), int(cg[k, j])
+        # the oracle's loop on the first j + 1 and on the first j columns of the row: the
+        # difference of the two summed losses is 1/2 E_j^2, and |w_j - q_j| = |E_j| U_jj
+        _, _, l1 = orc.quantize_layer(W_rows[k:k + 1, :j + 1], U[:j + 1, :j + 1], G[k:k + 1], "nu", cfg.bits, B=cfg.block)
+        l0 = orc.quantize_layer(W_rows[k:k + 1, :j], U[:j, :j], G[k:k + 1], "nu", cfg.bits, B=cfg.block)[2] if j else np.zeros(1)
+        dist = np.sqrt(2.0 * max(l1[0] - l0[0], 0.0)) * U[j, j]
+        step = abs(G[k, b] - G[k, a])
+        margin = (0.5 * step - dist) / step
+        _say(f"    row {rows[k]}: first difference at column {j} (codes {a} / {b}), {int((cg[k] != codes_ref[k]).sum())} codes "
+             f"differ, oracle's margin to the midpoint {margin:.2e} of a step, row loss ratio {rl[k] / loss_ref[k]:.4f}")
+        assert abs(a - b) == 1 and abs(margin) <= 1e-3
+        assert abs(rl[k] / loss_ref[k] - 1.0) < 5e-2
+    same = np.setdiff1d(np.arange(rows.size), differs)
+    assert np.max(np.abs(rl[same] / loss_ref[same] - 1.0)) < 1e-3
+    agree = hx.code_agreement(cg, codes_ref)
+    l_gpu = orc.layer_loss(W_rows, Wq.cpu().numpy()[rows], H)
+    l_ref = orc.layer_loss(W_rows, What, H)
+    _say(f"    {differs.size} of {rows.size} rows leave the oracle's codes at a near-tie; codes equal {agree:.5f}, loss gpu/ref {l_gpu / l_ref:.6f}")
+    assert differs.size <= 4 and agree >= 0.995 and abs(l_gpu / l_ref - 1.0) < 1e-3
+
+
 def test_config4_shape_affine_group128():
     cfg = lq_synth.CONFIGS["c4"].scaled(n_tokens=32768, r=4096)
     P = hx.params_for(cfg)
