@@ -528,6 +528,266 @@ __global__ __launch_bounds__(NTA) void affine_search_kernel(const float* __restr
   if (tid == 0) { out[0] = (float)sBestS[0]; out[1] = (float)sBestZ[0]; }
 }
 
+// ------------------------------------------------------------ affine: search on a sorted group
+// The same search (distinct (s, Z) classes, same keys, same minimizer) with the cost of a
+// candidate made independent of the group size.  The group is sorted once.  For a scale S the
+// weights that round to level j are a contiguous run of the sorted group, bounded by the
+// thresholds (j - 1/2) S and (j + 1/2) S, and the objective of Eq. 7 over a run that takes the
+// value q is  q^2 sum(omega) - 2 q sum(omega x) + sum(omega x^2),  three differences of prefix
+// sums (x = w - min of the group).  The runs do not depend on the zero-point: Z only decides
+// below and above which level everything is clipped.  So for one S the 2^b - 2 + n_Z
+// thresholds involved are located by binary search (all of them in step, so the LDS round
+// trips overlap), one walk over them accumulates the level terms, and each of the n_Z
+// zero-points is closed with its two clipped tails: O((2^b + n_Z) log g) per scale instead of
+// O(g n_Z).
+// The closed form cancels (its terms are of the size of sum(omega x^2), the loss is not), so
+// it ranks the candidates to about 1e-10 relative and is not used for the decision itself:
+// every lane's best candidate that lies within 1e-7 of the smallest value found is scored
+// again by the plain evaluation in the original order, and those plain losses decide, with
+// the same tie key as the enumeration.
+template <int NTA, int BITS>
+__global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restrict__ W, int64_t c,
+                                                            int64_t ldw, int g, int n2, int ngroups,
+                                                            const double* __restrict__ om64, int T,
+                                                            int t, float* __restrict__ SZ) {
+  constexpr int NW = NTA / 64;
+  constexpr int QM = (1 << BITS) - 1;
+  extern __shared__ __align__(16) unsigned char smraw[];
+  double2* sPAB = reinterpret_cast<double2*>(smraw);                         // [g + 1] prefix sums
+  unsigned long long* sKey = reinterpret_cast<unsigned long long*>(sPAB + (g + 1));   // [n2]
+  double* sOm = reinterpret_cast<double*>(sKey + n2);                        // [g] original order
+  float* sW = reinterpret_cast<float*>(sOm + g);                             // [g] original order
+  float* sSw = sW + g;                                                       // [n2] sorted, +inf padded
+  __shared__ float sRed[2 * NW];
+  __shared__ double sTot[3];
+  __shared__ double sBestLoss[NTA];
+  __shared__ int sBestKey[NTA];
+  __shared__ double sBestS[NTA], sBestZ[NTA];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t row = blockIdx.x / ngroups;
+  const int gi = blockIdx.x % ngroups;
+  const float* wsrc = W + row * ldw + (int64_t)gi * g;
+
+  float lo = INFINITY, hi = -INFINITY;
+  for (int i = tid; i < g; i += NTA) {
+    const float x = wsrc[i];
+    sW[i] = x;
+    sOm[i] = om64[(int64_t)gi * g + i];
+    lo = fminf(lo, x);
+    hi = fmaxf(hi, x);
+  }
+  // sort keys: the weight as an order-preserving 32-bit integer, then its position
+  for (int i = tid; i < n2; i += NTA) {
+    unsigned long long k = ~0ull;
+    if (i < g) {
+      const uint32_t u = __float_as_uint(wsrc[i]);
+      const uint32_t o = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+      k = ((unsigned long long)o << 32) | (unsigned)i;
+    }
+    sKey[i] = k;
+  }
+  lo = wave_min(lo);
+  hi = wave_max(hi);
+  if (lane == 0) { sRed[wave] = lo; sRed[NW + wave] = hi; }
+  __syncthreads();
+  float lof = sRed[0], hif = sRed[NW];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) { lof = fminf(lof, sRed[w]); hif = fmaxf(hif, sRed[NW + w]); }
+  const double lo0 = (double)lof;
+  const double hi0 = (double)hif;
+  const double R = hi0 - lo0;
+  float* out = SZ + (row * ngroups + gi) * 2;
+  if (R == 0.0) {  // constant group
+    if (tid == 0) { out[0] = 1.0f; out[1] = 0.0f; }
+    return;
+  }
+  // ---- bitonic sort of the keys (ascending)
+  for (int k = 2; k <= n2; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int i = tid; i < (n2 >> 1); i += NTA) {
+        const int a = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+        const int b = a | j;
+        const bool asc = (a & k) == 0;
+        const unsigned long long x = sKey[a], y = sKey[b];
+        if ((x > y) == asc) { sKey[a] = y; sKey[b] = x; }
+      }
+      __syncthreads();
+    }
+  }
+  for (int i = tid; i < n2; i += NTA) sSw[i] = (i < g) ? sW[(int)(sKey[i] & 0xffffffffull)] : INFINITY;
+  __syncthreads();
+  // ---- prefix sums of omega and omega x over the sorted group, total of omega x^2 (wavefront 0:
+  // a lane takes a contiguous piece, the pieces are chained by a scan across the lanes)
+  if (wave == 0) {
+    const int per = (g + 63) / 64;
+    const int i0 = lane * per, i1 = min(g, i0 + per);
+    double a = 0.0, b = 0.0, cc = 0.0;
+    for (int i = i0; i < i1; ++i) {
+      const double om = sOm[(int)(sKey[i] & 0xffffffffull)];
+      const double x = (double)sSw[i] - lo0;
+      a += om;
+      b = fma(om, x, b);
+      cc = fma(om * x, x, cc);
+    }
+    double ea = a, eb = b, ec = cc;      // inclusive scan over the lanes
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const double ta = __shfl_up(ea, o, 64), tb = __shfl_up(eb, o, 64), tc = __shfl_up(ec, o, 64);
+      if (lane >= o) { ea += ta; eb += tb; ec += tc; }
+    }
+    // sums of the lanes before this one = the inclusive value of the previous lane
+    double ra = __shfl_up(ea, 1, 64), rb = __shfl_up(eb, 1, 64);
+    if (lane == 0) { ra = 0.0; rb = 0.0; }
+    if (lane == 0) sPAB[0] = make_double2(0.0, 0.0);
+    for (int i = i0; i < i1; ++i) {
+      const double om = sOm[(int)(sKey[i] & 0xffffffffull)];
+      const double x = (double)sSw[i] - lo0;
+      ra += om;
+      rb = fma(om, x, rb);
+      sPAB[i + 1] = make_double2(ra, rb);
+    }
+    if (lane == 63) { sTot[0] = ea; sTot[1] = eb; sTot[2] = ec; }
+  }
+  __syncthreads();
+  const double Atot = sTot[0], Btot = sTot[1], Ctot = sTot[2];
+
+  const double qmax = (double)QM;
+  const double dT = (double)T;
+  AffBest best;
+  best.loss = INFINITY; best.key = 0x7fffffff; best.S = 1.0; best.Z = 0.0;
+
+  // One chunk of up to NZC consecutive zero-points zb, zb - 1, ... of scale S: thresholds,
+  // positions, walk.
+  auto chunk = [&](auto nzc_tag, double S, double zb, double* loss) {
+    constexpr int NZC = decltype(nzc_tag)::value;
+    constexpr int NB = QM + NZC - 1;
+    const double jmin = -zb;                      // lowest level of the chunk
+    float thr[NB];
+    int pos[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const double td = (jmin + (double)i + 0.5) * S;
+      float tf = (float)td;
+      if ((double)tf < td) {                      // smallest float >= td: w < td exactly when w < tf
+        uint32_t u = __float_as_uint(tf);
+        u = (tf >= 0.0f) ? (((u & 0x7fffffffu) == 0u) ? 1u : u + 1u) : u - 1u;
+        tf = __uint_as_float(u);
+      }
+      thr[i] = tf;
+      pos[i] = 0;
+    }
+    for (int step = n2 >> 1; step > 0; step >>= 1) {
+#pragma unroll
+      for (int i = 0; i < NB; ++i) pos[i] += (sSw[pos[i] + step - 1] < thr[i]) ? step : 0;
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) pos[i] += (sSw[pos[i]] < thr[i]) ? 1 : 0;   // pos = weights below thr
+    // (all NB steps always run: with every index a compile-time constant the arrays stay in
+    // registers; steps beyond the zero-points in use only fill entries nobody reads)
+    double F = 0.0, pA = 0.0, pB = 0.0;
+    double lossA[NZC];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const double2 ab = sPAB[pos[i]];
+      const double lev = jmin + (double)i;
+      const double q = fma(lev, S, -lo0);         // level jmin + i in shifted coordinates
+      if (i >= 1) {
+        F = fma(q * q, ab.x - pA, F);
+        F = fma(-2.0 * q, ab.y - pB, F);
+      }
+      if (i < NZC) lossA[i] = fma(q * q, ab.x, Ctot) - 2.0 * q * ab.y - F;
+      if (i >= QM - 1) {
+        const double qh = fma(lev + 1.0, S, -lo0);
+        loss[i - (QM - 1)] = lossA[i - (QM - 1)] + (F + qh * qh * (Atot - ab.x) - 2.0 * qh * (Btot - ab.y));
+      }
+      pA = ab.x;
+      pB = ab.y;
+    }
+  };
+
+  const int rounds = (2 * t + NTA) / NTA;
+  for (int rd = 0; rd < rounds; ++rd) {
+    const int s = tid + rd * NTA;
+    const bool live = s <= 2 * t;
+    const int ta = (s > t) ? (s - t) : 0;      // smallest t_min with t_max = s - t_min <= t
+    const int tb = (s < t) ? s : t;            // largest t_min
+    const double lo_a = lo0 + (double)ta * R / dT;
+    const double hi_a = hi0 - (double)(s - ta) * R / dT;
+    const double S = (hi_a - lo_a) / qmax;
+    const bool ok = live && (S > 0.0);
+    const double Sx = ok ? S : 1.0;
+    const double lo_b = lo0 + (double)tb * R / dT;
+    const double zf = -rint(lo_a / Sx);
+    const double zl = -rint(lo_b / Sx);
+    double span = zf - zl;
+    if (!(span >= 0.0)) span = 0.0;
+    const int nz = ok ? (int)fmin(span, 1.0e6) + 1 : 0;
+    int nzw = nz;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) nzw = max(nzw, __shfl_xor(nzw, o, 64));
+    for (int z0 = 0; z0 < nzw; z0 += 8) {
+      double loss[8];
+      const int cntw = min(8, nzw - z0);
+      const double zb = zf - (double)z0;
+      if (cntw <= 4) chunk(std::integral_constant<int, 4>{}, Sx, zb, loss);
+      else chunk(std::integral_constant<int, 8>{}, Sx, zb, loss);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int zi = z0 + k;
+        if (k < cntw && zi < nz) {
+          const double Z = zf - (double)zi;
+          // first t_min of this class: smallest t_min >= ta with round(lo / S) == -Z
+          int tf = ta;
+          if (zi > 0) {
+            tf = (int)ceil(((-Z - 0.5) * S - lo0) * dT / R);
+            tf = tf < ta ? ta : (tf > tb ? tb : tf);
+          }
+          const int key = tf * (t + 1) + (s - tf);
+          if (aff_better(loss[k], key, best)) { best.loss = loss[k]; best.key = key; best.S = S; best.Z = Z; }
+        }
+      }
+    }
+  }
+  // ---- smallest closed-form value of the workgroup; candidates within its noise are scored plainly
+  sBestLoss[tid] = best.loss;
+  __syncthreads();
+  for (int w2 = NTA / 2; w2 > 0; w2 >>= 1) {
+    if (tid < w2) sBestLoss[tid] = fmin(sBestLoss[tid], sBestLoss[tid + w2]);
+    __syncthreads();
+  }
+  const double lmin = sBestLoss[0];
+  __syncthreads();
+  double exact = INFINITY;
+  if (best.loss <= lmin + (1.0e-7 * fabs(lmin) + 1.0e-12 * Ctot)) {
+    const double S = best.S, Z = best.Z;
+    const double invS = 1.0 / S;
+    const double cl = -Z, ch = qmax - Z;
+    double loss = 0.0;
+    for (int i = 0; i < g; ++i) {
+      const double w = (double)sW[i];
+      const double u = fmin(fmax(rint(w * invS), cl), ch);
+      const double dlt = fma(u, S, -w);
+      loss = fma(sOm[i] * dlt, dlt, loss);
+    }
+    exact = loss;
+  }
+  sBestLoss[tid] = exact; sBestKey[tid] = best.key; sBestS[tid] = best.S; sBestZ[tid] = best.Z;
+  __syncthreads();
+  for (int w2 = NTA / 2; w2 > 0; w2 >>= 1) {
+    if (tid < w2) {
+      AffBest o;
+      o.loss = sBestLoss[tid]; o.key = sBestKey[tid];
+      if (aff_better(sBestLoss[tid + w2], sBestKey[tid + w2], o)) {
+        sBestLoss[tid] = sBestLoss[tid + w2]; sBestKey[tid] = sBestKey[tid + w2];
+        sBestS[tid] = sBestS[tid + w2]; sBestZ[tid] = sBestZ[tid + w2];
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) { out[0] = (float)sBestS[0]; out[1] = (float)sBestZ[0]; }
+}
+
 template <int K>
 lq_status launch_kmeans(const float* W, int64_t r, int64_t c, int64_t ldw, const float* om32,
                         const float* init, int max_iter, float* G, int* next_row, hipStream_t st) {
@@ -658,7 +918,6 @@ lq_status fit_grid_impl(const float* W, int64_t r, int64_t c, int64_t ldw, const
   if (r * ngroups > 0x7fffffffLL) return lq::fail(LQ_ERR_UNSUPPORTED, "lq_fit_grid: more than 2^31 groups");
   hipLaunchKernelGGL(importance_kernel, dim3(1), dim3(1024), 0, st, hinv_diag, c, P->p, om32, om64, next_row);
   LQ_CHECK_LAUNCH("importance_kernel");
-  const size_t lds = (size_t)g * 2 * sizeof(double);
   const int t = lq::resolve_t(P);
   const int ns = 2 * t + 1;
   // threads per group: fewest idle lanes in the last round of s values; ties go to the larger
@@ -670,6 +929,38 @@ lq_status fit_grid_impl(const float* W, int64_t r, int64_t c, int64_t ldw, const
       if (padded < best) { best = padded; nta = cand; }
     }
   }
+  const dim3 ggrid((unsigned)(r * ngroups));
+  // The sorted-group kernel covers the fine partitions (every integer between the end values
+  // of the zero-point occurs: T - 2t > 2^b - 1) on groups of up to SORT_MAX_G columns.
+  constexpr int64_t SORT_MAX_G = 2048;
+  const bool dense = (P->T - 2 * t) > ((1 << P->bits) - 1);
+  if (dense && g <= SORT_MAX_G) {
+    int n2 = 1;
+    while (n2 < g) n2 <<= 1;
+    const size_t lds_sorted = (size_t)(g + 1) * 16 + (size_t)n2 * 8 + (size_t)g * 12 + (size_t)n2 * 4;
+    static lq::DeviceOnce sorted_once;
+    if (lq::DeviceOnceGuard once(sorted_once); once.first()) {
+      const int lim = (int)((SORT_MAX_G + 1) * 16 + SORT_MAX_G * 8 + SORT_MAX_G * 12 + SORT_MAX_G * 4);
+#define LQ_ATTR(N, BT) LQ_CHECK_HIP(hipFuncSetAttribute((const void*)affine_sorted_kernel<N, BT>, \
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, lim))
+      LQ_ATTR(64, 2); LQ_ATTR(64, 3); LQ_ATTR(64, 4);
+      LQ_ATTR(128, 2); LQ_ATTR(128, 3); LQ_ATTR(128, 4);
+      LQ_ATTR(256, 2); LQ_ATTR(256, 3); LQ_ATTR(256, 4);
+#undef LQ_ATTR
+      once.done();
+    }
+#define LQ_AFS(N, BT) hipLaunchKernelGGL((affine_sorted_kernel<N, BT>), ggrid, dim3(N), lds_sorted, st, W, c, ldw, \
+                                         (int)g, n2, (int)ngroups, (const double*)om64, P->T, t, grid)
+#define LQ_AFS_N(N) do { if (P->bits == 2) LQ_AFS(N, 2); else if (P->bits == 3) LQ_AFS(N, 3); else LQ_AFS(N, 4); } while (0)
+    if (nta == 64) LQ_AFS_N(64);
+    else if (nta == 128) LQ_AFS_N(128);
+    else LQ_AFS_N(256);
+#undef LQ_AFS_N
+#undef LQ_AFS
+    LQ_CHECK_LAUNCH("affine_sorted_kernel");
+    return LQ_OK;
+  }
+  const size_t lds = (size_t)g * 2 * sizeof(double);
   static lq::DeviceOnce attr_once;
   if (lq::DeviceOnceGuard once(attr_once); once.first()) {
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)affine_search_kernel<64>,
@@ -680,7 +971,6 @@ lq_status fit_grid_impl(const float* W, int64_t r, int64_t c, int64_t ldw, const
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)(8192 * 16)));
     once.done();
   }
-  const dim3 ggrid((unsigned)(r * ngroups));
 #define LQ_AFF(N) hipLaunchKernelGGL(affine_search_kernel<N>, ggrid, dim3(N), lds, st, W, c, ldw, (int)g, \
                                      (int)ngroups, (const double*)om64, P->bits, P->T, t, grid)
   if (nta == 64) LQ_AFF(64);

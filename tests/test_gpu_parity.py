@@ -272,13 +272,18 @@ def test_small_affine_end_to_end():
     cfg = lq_synth.CONFIGS["c4"].scaled(name="c4s", r=24, c=512, n_tokens=4096, x_outlier_channels=8, T=256)
     _say("end-to-end small affine")
     W, H, out, ref = _full_pass(cfg, hx.params_for(cfg))
-    ok = hx.aff_grid_match(out["grid"], ref["grid"])
-    agree = hx.code_agreement(out["codes"], ref["codes"])
+    # Groups in which a few high-importance weights round to level 0 for many (S, Z) have many
+    # candidates within 1e-9 of the minimum of Eq. 7; a group that takes another of them must
+    # score within 1e-5 of the oracle's (float64), and its row is then compared with the oracle's
+    # column loop run from the device's grids.
+    share, agree, redone = hx.compare_rows_strict("aff", cfg.bits, W, ref["d"], ref["U"], out["grid"], out["codes"],
+                                                  ref["grid"], ref["codes"], p=cfg.p, group_size=cfg.group_size,
+                                                  B=cfg.block, say=_say)
     l_gpu = orc.layer_loss(W, out["W_hat"], H)
     l_ref = orc.layer_loss(W, ref["W_hat"], H)
-    _say(f"  groups {ok.mean():.4f} codes {agree:.5f} loss ratio {l_gpu / l_ref:.6f}")
-    assert ok.mean() >= 0.97
-    assert agree >= 0.99
+    _say(f"  groups {share:.4f} codes {agree:.5f} ({redone} rows from the device's grids) loss ratio {l_gpu / l_ref:.6f}")
+    assert share >= 0.97
+    assert agree >= 0.999
     assert abs(l_gpu / l_ref - 1.0) < 2e-3
 
 
