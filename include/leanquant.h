@@ -13,8 +13,9 @@
  * Around them: lq_hessian_accumulate_host (line 3 with X streamed from host memory),
  * lq_fit_grid_from / lq_kmeanspp_seed (Lloyd iteration from another start, the k-means++
  * seeding of the paper's initialisation table), lq_quantize_exact / lq_hinv_from_factor
- * (Algorithm 2, LeanQuant-Exact), lq_pack_layer / lq_unpack_layer / lq_matvec_packed (the
- * stored form behind the "Bits" columns of the result tables and the product with it).
+ * (Algorithm 2, LeanQuant-Exact), lq_pack_layer / lq_unpack_layer / lq_matvec_packed /
+ * lq_matmul_packed (the stored form behind the "Bits" columns of the result tables and the
+ * products with it).
  *
  * Conventions shared by all calls
  *   - Every pointer is a DEVICE pointer unless the comment says "host".  The
@@ -288,6 +289,18 @@ lq_status lq_unpack_layer(const uint8_t* packed, int64_t packed_ld, const uint16
  * most 16384; affine groups multiples of 32 columns.  No workspace.
  */
 lq_status lq_matvec_packed(const uint8_t* packed, int64_t packed_ld, const uint16_t* table, int64_t r,
+                           int64_t c, const lq_params* P, const float* X, int64_t nb, float* Y,
+                           void* stream);
+
+/*
+ * The same product for a batch (the GEMM form): Y[n][k] = sum_j W_hat[k][j] X[n][j] for nb input
+ * vectors, with the stored weights decoded once per 32 or 64 vectors into fp32 tiles in LDS and
+ * multiplied on the fp32 matrix cores, fp32 accumulation in a fixed order.  Arguments, layouts
+ * and alignment as lq_matvec_packed (X [nb x c], Y [nb x r]); c a multiple of 32 (no upper
+ * limit), affine groups multiples of 32 columns.  Meant for nb >= 16: below that
+ * lq_matvec_packed's passes over the codes are faster.  No workspace.
+ */
+lq_status lq_matmul_packed(const uint8_t* packed, int64_t packed_ld, const uint16_t* table, int64_t r,
                            int64_t c, const lq_params* P, const float* X, int64_t nb, float* Y,
                            void* stream);
 

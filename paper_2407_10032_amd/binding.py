@@ -24,7 +24,7 @@ LQ_CALL_HESSIAN, LQ_CALL_CHOLESKY, LQ_CALL_FIT_GRID, LQ_CALL_QUANTIZE, LQ_CALL_E
 EXPORTS = ("lq_params_default", "lq_hessian_accumulate", "lq_hessian_accumulate_host",
            "lq_hessian_host_workspace_bytes", "lq_cholesky_inv", "lq_fit_grid",
            "lq_fit_grid_static", "lq_fit_grid_from", "lq_kmeanspp_seed", "lq_quantize_layer", "lq_quantize_exact", "lq_hinv_from_factor", "lq_packed_row_bytes", "lq_bits_per_weight", "lq_pack_layer",
-           "lq_unpack_layer", "lq_matvec_packed", "lq_workspace_bytes", "lq_last_error", "lq_version")
+           "lq_unpack_layer", "lq_matvec_packed", "lq_matmul_packed", "lq_workspace_bytes", "lq_last_error", "lq_version")
 
 
 class lq_params(ctypes.Structure):
@@ -88,6 +88,8 @@ def load() -> ctypes.CDLL:
     lib.lq_unpack_layer.restype = ctypes.c_int
     lib.lq_matvec_packed.argtypes = [vp, i64, vp, i64, i64, pp, vp, i64, vp, vp]
     lib.lq_matvec_packed.restype = ctypes.c_int
+    lib.lq_matmul_packed.argtypes = [vp, i64, vp, i64, i64, pp, vp, i64, vp, vp]
+    lib.lq_matmul_packed.restype = ctypes.c_int
     lib.lq_workspace_bytes.argtypes = [ctypes.c_int, i64, i64, i64, pp]
     lib.lq_workspace_bytes.restype = sz
     lib.lq_last_error.argtypes = []
@@ -339,6 +341,18 @@ def lq_matvec_packed(packed: torch.Tensor, table: torch.Tensor, c: int, P: lq_pa
     if not X.is_contiguous() or not Y.is_contiguous() or X.shape[1] != c or tuple(Y.shape) != (nb, r):
         raise ValueError("X must be contiguous [nb x c] and Y contiguous [nb x r]")
     _check(load().lq_matvec_packed(_ptr(packed, torch.uint8, "packed"), _ld(packed, "packed"),
+                                   _ptr(table, torch.int16, "table"), r, c, ctypes.byref(P),
+                                   _ptr(X, torch.float32, "X"), nb, _ptr(Y, torch.float32, "Y"), _stream()))
+
+
+def lq_matmul_packed(packed: torch.Tensor, table: torch.Tensor, c: int, P: lq_params,
+                     X: torch.Tensor, Y: torch.Tensor) -> None:
+    """Y [nb x r] = X [nb x c] times the transposed stored layer, batched form (fp32 MFMA)."""
+    r = packed.shape[0]
+    nb = X.shape[0]
+    if not X.is_contiguous() or not Y.is_contiguous() or X.shape[1] != c or tuple(Y.shape) != (nb, r):
+        raise ValueError("X must be contiguous [nb x c] and Y contiguous [nb x r]")
+    _check(load().lq_matmul_packed(_ptr(packed, torch.uint8, "packed"), _ld(packed, "packed"),
                                    _ptr(table, torch.int16, "table"), r, c, ctypes.byref(P),
                                    _ptr(X, torch.float32, "X"), nb, _ptr(Y, torch.float32, "Y"), _stream()))
 

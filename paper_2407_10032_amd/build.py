@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libleanquant.so")
 SOURCES = ["quantize_col128.hip", "quantize_col64.hip", "quantize_col32.hip", "api.hip", "hessian.hip",
-           "cholesky.hip", "fit_grid.hip", "quantize.hip", "pack.hip", "exact.hip", "gemv.hip", "seed.hip"]
+           "cholesky.hip", "fit_grid.hip", "quantize.hip", "pack.hip", "exact.hip", "gemv.hip", "gemm_packed.hip", "seed.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

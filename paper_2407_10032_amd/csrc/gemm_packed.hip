@@ -1,0 +1,204 @@
+// lq_matmul_packed: Y = X W_hat^T for a batch of input vectors, straight from the stored form
+// of a quantized layer (packed b-bit codes + binary16 tables) -- the batched form of the
+// decoding-time product that the paper's appendix on inference efficiency builds a kernel
+// for.  lq_matvec_packed walks the codes once per 4 vectors on the vector ALU; here a weight
+// is decoded once per 32 or 64 vectors into an fp32 tile in LDS and the products run on the
+// fp32 matrix cores (v_mfma_f32_32x32x2_f32), fp32 accumulation in a fixed order.
+//
+// A workgroup (4 wavefronts) owns 128 rows of W_hat and 32 MT input vectors (MT = 1 or 2) and
+// walks the columns in stages of 64:
+//   * decode: thread (row, unit) loads one unit of 32 codes (16 / 12 / 8 bytes), turns each
+//     code into its weight -- table lookup in LDS (non-uniform) or fma(code, S, -Z S) with the
+//     unit's group pair (affine) -- and writes the 32 floats into the row of the LDS tile;
+//   * the X tile is copied as it lies in memory (vectors are rows);
+//   * both tiles have odd row strides (65 floats), so the MFMA operand reads -- lane l takes
+//     element (row l % 32, column 2 kk + l / 32) -- hit 32 distinct banks, and the k loop holds
+//     nothing but LDS reads with immediate offsets and MFMAs;
+//   * wavefront w multiplies the X tile with rows 32 w .. 32 w + 31 of the weight tile; its
+//     accumulators are Y[vector][row] with the row index along the lanes, so the final stores
+//     are 128-byte runs of a vector's outputs.
+// The loads of the next stage (codes, group pairs, X) are issued before the current stage's
+// MFMA loop.  Two or three workgroups share a compute unit, so one decodes while another
+// multiplies.
+#include <hip/hip_fp16.h>
+
+#include "lq_common.h"
+#include "lq_mfma.h"
+#include "lq_unpack.h"
+
+namespace {
+
+using lq::floatx16;
+using lq::UNIT;
+
+constexpr int NT = 256;
+constexpr int KS = 64;          // columns per stage (two units)
+constexpr int WROWS = 128;      // rows of W_hat per workgroup
+constexpr int LDT = KS + 1;     // row stride of the LDS tiles
+
+struct MmArgs {
+  const uint8_t* packed; int64_t packed_ld;
+  const uint16_t* table;
+  const float* x;      // [nb x c]
+  float* y;            // [nb x r]
+  int64_t r; int c; int64_t nb;
+  int group; int ngroups;
+};
+
+template <int BITS, bool AFF, int J>
+__device__ __forceinline__ void decode_unit(const uint32_t (&w)[BITS], const float* lut, float S, float ZS,
+                                            bool valid, float* dst) {
+  if constexpr (J < UNIT) {
+    const uint32_t code = lq::unit_code<BITS, J>(w);
+    // Section 2.1: table[code], or (w_int - Z) S
+    float v = AFF ? fmaf((float)code, S, -ZS) : lut[code];
+    dst[J] = valid ? v : 0.0f;
+    decode_unit<BITS, AFF, J + 1>(w, lut, S, ZS, valid, dst);
+  }
+}
+
+template <int BITS, bool AFF, int MT>
+__global__ __launch_bounds__(NT, 2) void matmul_packed_kernel(MmArgs a) {
+  constexpr int K = 1 << BITS;
+  constexpr int UB = UNIT * BITS / 8;                  // bytes per unit
+  constexpr int XROWS = 32 * MT;
+  constexpr int XQ = XROWS * (KS / 4) / NT;            // float4 loads of the X tile per thread
+  __shared__ float sW[WROWS * LDT];
+  __shared__ float sX[XROWS * LDT];
+  __shared__ float sLut[AFF ? 1 : WROWS * K];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ml = lane & 31, hl = lane >> 5;
+  const int64_t row0 = (int64_t)blockIdx.x * WROWS;
+  const int64_t n0 = (int64_t)blockIdx.y * XROWS;
+  const int nunits = a.c / UNIT;
+
+  // decode assignment: thread -> (row of the tile, first or second unit of the stage); rows
+  // past r read row r - 1 (their results are never stored)
+  const int drow = tid >> 1, dunit = tid & 1;
+  int64_t grow = row0 + drow;
+  grow = grow < a.r ? grow : a.r - 1;
+  const uint8_t* prow = a.packed + grow * a.packed_ld;
+
+  if (!AFF) {
+    for (int i = tid; i < WROWS * K; i += NT) {
+      int64_t rr = row0 + i / K;
+      rr = rr < a.r ? rr : a.r - 1;
+      sLut[i] = __half2float(__ushort_as_half(a.table[rr * K + i % K]));
+    }
+  }
+
+  uint32_t wreg[BITS];
+  uint32_t szreg = 0;
+  float4 xreg[XQ];
+  bool uok = false;
+  auto prefetch = [&](int k0) {
+    const int u = k0 / UNIT + dunit;
+    uok = u < nunits;
+    const int uu = uok ? u : nunits - 1;
+    lq::load_unit<BITS>(prow + (int64_t)uu * UB, wreg);
+    // affine: binary16 S | int16 Z << 16 of the unit's group
+    if (AFF) szreg = *reinterpret_cast<const uint32_t*>(a.table + (grow * a.ngroups + (uu * UNIT) / a.group) * 2);
+#pragma unroll
+    for (int q = 0; q < XQ; ++q) {
+      const int idx = tid + q * NT;
+      const int n = idx / (KS / 4), k4 = idx % (KS / 4);
+      const int64_t gn = n0 + n;
+      const int kcol = k0 + 4 * k4;
+      xreg[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (gn < a.nb && kcol < a.c) xreg[q] = *reinterpret_cast<const float4*>(a.x + gn * a.c + kcol);
+    }
+  };
+
+  floatx16 acc[MT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[m][v] = 0.0f;
+
+  prefetch(0);
+  for (int k0 = 0; k0 < a.c; k0 += KS) {
+    __syncthreads();                 // the previous stage's operand reads are done (first pass: the table is in LDS)
+    {
+      float S = 1.0f, ZS = 0.0f;
+      if (AFF) {
+        S = __half2float(__ushort_as_half((uint16_t)(szreg & 0xffffu)));
+        ZS = (float)(int16_t)(szreg >> 16) * S;
+      }
+      decode_unit<BITS, AFF, 0>(wreg, sLut + (AFF ? 0 : drow * K), S, ZS, uok, sW + drow * LDT + dunit * UNIT);
+#pragma unroll
+      for (int q = 0; q < XQ; ++q) {
+        const int idx = tid + q * NT;
+        const int n = idx / (KS / 4), k4 = idx % (KS / 4);
+        float* d = sX + n * LDT + 4 * k4;
+        d[0] = xreg[q].x; d[1] = xreg[q].y; d[2] = xreg[q].z; d[3] = xreg[q].w;
+      }
+    }
+    __syncthreads();
+    if (k0 + KS < a.c) prefetch(k0 + KS);
+    const float* pb = sW + (32 * wave + ml) * LDT + hl;
+    const float* pa = sX + ml * LDT + hl;
+#pragma unroll
+    for (int kk = 0; kk < KS / 2; ++kk) {
+      const float b = pb[2 * kk];
+#pragma unroll
+      for (int m = 0; m < MT; ++m)
+        acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[m * 32 * LDT + 2 * kk], b, acc[m], 0, 0, 0);
+    }
+  }
+
+  const int64_t row = row0 + 32 * wave + ml;
+  if (row < a.r) {
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int64_t n = n0 + 32 * m + 8 * (v >> 2) + 4 * hl + (v & 3);
+        if (n < a.nb) a.y[n * a.r + row] = acc[m][v];
+      }
+    }
+  }
+}
+
+template <int BITS, bool AFF>
+void launch_mm(const MmArgs& a, hipStream_t st) {
+  const unsigned gx = (unsigned)lq::ceil_div(a.r, WROWS);
+  if (a.nb <= 32) {
+    hipLaunchKernelGGL((matmul_packed_kernel<BITS, AFF, 1>), dim3(gx, (unsigned)lq::ceil_div(a.nb, 32)), dim3(NT), 0, st, a);
+  } else {
+    hipLaunchKernelGGL((matmul_packed_kernel<BITS, AFF, 2>), dim3(gx, (unsigned)lq::ceil_div(a.nb, 64)), dim3(NT), 0, st, a);
+  }
+}
+
+}  // namespace
+
+extern "C" lq_status lq_matmul_packed(const uint8_t* packed, int64_t packed_ld, const uint16_t* table,
+                                      int64_t r, int64_t c, const lq_params* P, const float* X,
+                                      int64_t nb, float* Y, void* stream) {
+  if (r < 0 || c < 1 || nb < 0) return lq::fail(LQ_ERR_INVALID_ARG, "lq_matmul_packed: r=%lld c=%lld nb=%lld", (long long)r, (long long)c, (long long)nb);
+  lq_status stt = lq::check_params(P, c);
+  if (stt != LQ_OK) return stt;
+  if (r == 0 || nb == 0) return LQ_OK;
+  if (!packed || !table || !X || !Y) return lq::fail(LQ_ERR_INVALID_ARG, "lq_matmul_packed: null pointer");
+  const int64_t row_bytes = (c * P->bits + 7) / 8;
+  if (packed_ld < row_bytes) return lq::fail(LQ_ERR_INVALID_ARG, "lq_matmul_packed: packed_ld too small");
+  const int align = P->bits == 4 ? 16 : (P->bits == 2 ? 8 : 4);
+  if (c % UNIT != 0 || c > (1 << 30))
+    return lq::fail(LQ_ERR_UNSUPPORTED, "lq_matmul_packed: c must be a multiple of %d", UNIT);
+  if (packed_ld % align != 0 || !lq::aligned(packed, align) || !lq::aligned(X, 16) || !lq::aligned(table, 4))
+    return lq::fail(LQ_ERR_UNSUPPORTED, "lq_matmul_packed: packed rows must be %d-byte aligned, X 16-byte aligned", align);
+  if (nb > 65535LL * 64) return lq::fail(LQ_ERR_UNSUPPORTED, "lq_matmul_packed: nb too large for one launch");
+  const bool aff = P->mode == LQ_GRID_AFFINE;
+  const int64_t g = (aff && P->group_size > 0) ? P->group_size : c;
+  if (aff && g % UNIT != 0) return lq::fail(LQ_ERR_UNSUPPORTED, "lq_matmul_packed: affine groups must be multiples of %d columns", UNIT);
+  MmArgs a;
+  a.packed = packed; a.packed_ld = packed_ld; a.table = table;
+  a.x = X; a.y = Y; a.r = r; a.c = (int)c; a.nb = nb;
+  a.group = (int)g; a.ngroups = (int)(c / g);
+  hipStream_t st = (hipStream_t)stream;
+  if (P->bits == 2) { if (aff) launch_mm<2, true>(a, st); else launch_mm<2, false>(a, st); }
+  else if (P->bits == 3) { if (aff) launch_mm<3, true>(a, st); else launch_mm<3, false>(a, st); }
+  else { if (aff) launch_mm<4, true>(a, st); else launch_mm<4, false>(a, st); }
+  LQ_CHECK_LAUNCH("matmul_packed_kernel");
+  return LQ_OK;
+}

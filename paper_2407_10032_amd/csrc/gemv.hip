@@ -13,11 +13,15 @@
 #include <hip/hip_fp16.h>
 
 #include "lq_common.h"
+#include "lq_unpack.h"
 
 namespace {
 
+using lq::UNIT;
+using lq::load_unit;
+using lq::unit_code;
+
 constexpr int NT = 256;
-constexpr int UNIT = 32;      // codes per lane and load
 
 struct MvArgs {
   const uint8_t* packed; int64_t packed_ld;
@@ -27,28 +31,6 @@ struct MvArgs {
   int64_t r; int c;
   int group; int ngroups;
 };
-
-template <int BITS>
-__device__ __forceinline__ void load_unit(const uint8_t* p, uint32_t (&w)[BITS]) {
-  if constexpr (BITS == 4) {
-    const uint4 v = *reinterpret_cast<const uint4*>(p);
-    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
-  } else if constexpr (BITS == 2) {
-    const uint2 v = *reinterpret_cast<const uint2*>(p);
-    w[0] = v.x; w[1] = v.y;
-  } else {
-    const uint32_t* q = reinterpret_cast<const uint32_t*>(p);
-    w[0] = q[0]; w[1] = q[1]; w[2] = q[2];
-  }
-}
-
-// code j (0..31) of a unit held as BITS 32-bit words of the little-endian bit stream
-template <int BITS, int J>
-__device__ __forceinline__ uint32_t unit_code(const uint32_t (&w)[BITS]) {
-  constexpr int pos = BITS * J, idx = pos / 32, sh = pos % 32;
-  if constexpr (sh + BITS <= 32) return (w[idx] >> sh) & ((1u << BITS) - 1u);
-  else return ((w[idx] >> sh) | (w[idx + 1] << (32 - sh))) & ((1u << BITS) - 1u);
-}
 
 // One unit of a row against the same 32 columns of NBV input vectors: a weight is decoded
 // once and used NBV times.

@@ -173,3 +173,52 @@ def test_matvec_from_the_stored_form(mode, bits, group, r, c, nb):
     err = np.abs(Y.cpu().numpy() - ref)
     # fp32 accumulation of c products: error within c eps of the absolute sum, far below in practice
     assert np.all(err <= 4e-6 * scale + 1e-30), float(np.max(err / (scale + 1e-30)))
+
+
+@pytest.mark.parametrize("mode,bits,group", [("nu", 4, 0), ("nu", 3, 0), ("nu", 2, 0),
+                                             ("aff", 4, 128), ("aff", 2, 64), ("aff", 3, 0)])
+@pytest.mark.parametrize("r,c,nb", [(37, 1024, 16), (200, 4096, 33), (130, 2048, 64), (64, 11008, 40),
+                                    (257, 160, 17), (16, 16384, 32), (300, 4128, 100), (5, 32, 1)])
+def test_matmul_from_the_stored_form(mode, bits, group, r, c, nb):
+    """The batched (matrix-core) product with a stored layer against the float64 oracle, at the
+    tolerance of the one-vector product: ragged row counts (tiles of 128), batches that are not
+    multiples of 32 / 64, column counts that are not multiples of the 64-column stage."""
+    lq = _lq()
+    if mode == "aff" and group and c % group:
+        pytest.skip("group does not divide c")
+    rng = np.random.default_rng(17 * bits + r + c + nb)
+    K = 1 << bits
+    codes = rng.integers(0, K, size=(r, c)).astype(np.uint8)
+    if mode == "nu":
+        grid = np.sort(rng.normal(0, 0.02, size=(r, K)), axis=1).astype(np.float32)
+        P = lq.lq_params_default(bits=bits, mode=lq.LQ_GRID_NONUNIFORM)
+    else:
+        ng = c // (group if group else c)
+        S = np.abs(rng.normal(0.01, 0.003, size=(r, ng))) + 1e-4
+        Z = rng.integers(-3, K + 3, size=(r, ng)).astype(np.float64)
+        grid = np.stack([S, Z], axis=-1).astype(np.float32)
+        P = lq.lq_params_default(bits=bits, mode=lq.LQ_GRID_AFFINE, group_size=group)
+    rb = lq.lq_packed_row_bytes(c, bits)
+    ld = (rb + 15) // 16 * 16
+    packed = torch.zeros((r, ld), dtype=torch.uint8, device="cuda")[:, :rb]
+    table = torch.empty(grid.size, dtype=torch.int16, device="cuda")
+    lq.lq_pack_layer(hx.to_dev(codes, torch.uint8), hx.to_dev(grid), P, packed, table)
+    X = rng.standard_normal((nb, c)).astype(np.float32)
+    Y = torch.full((nb, r), float("nan"), dtype=torch.float32, device="cuda")
+    lq.lq_matmul_packed(packed, table, c, P, hx.to_dev(X), Y)
+    torch.cuda.synchronize()
+    exp_packed = po.pack_codes(codes, bits)
+    exp_table = po.table_nu(grid) if mode == "nu" else po.table_aff(grid)
+    ref = po.matvec_packed(exp_packed, exp_table, X, c, bits, mode, group)
+    Wh = po.dequantize(exp_packed, exp_table, c, bits, mode, group).astype(np.float64)
+    scale = np.abs(X.astype(np.float64)) @ np.abs(Wh).T          # sum_j |w_kj| |x_j|
+    got = Y.cpu().numpy()
+    assert np.all(np.isfinite(got))
+    err = np.abs(got - ref)
+    assert np.all(err <= 4e-6 * scale + 1e-30), float(np.max(err / (scale + 1e-30)))
+    # and it agrees with the one-vector kernel far inside that tolerance (same weights, fp32 sums)
+    if c <= 16384:
+        Y1 = torch.empty((nb, r), dtype=torch.float32, device="cuda")
+        lq.lq_matvec_packed(packed, table, c, P, hx.to_dev(X), Y1)
+        torch.cuda.synchronize()
+        assert np.all(np.abs(got - Y1.cpu().numpy()) <= 4e-6 * scale + 1e-30)
