@@ -25,10 +25,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 FP32_MFMA_PEAK_TFLOPS = 157.3
-# HBM-side bytes of one Gram-kernel launch on the c2 workload, from the two rocprofv3 --pmc
-# runs (FETCH_SIZE, WRITE_SIZE, each scaled by a plain copy of known size) summarised in
-# profiles/bench_c2_gram_kernel_counters.md.  Only valid for that workload.
+# HBM-side bytes of one Gram-kernel launch on the c2 workload: NOT measured by this run (bench.py
+# cannot read hardware counters).  It is the figure of the two rocprofv3 --pmc runs of this very
+# command (FETCH_SIZE, then WRITE_SIZE, each scaled by a plain copy of known size) that
+# profiles/bench_c2_gram_kernel_counters.md summarises; only valid for that workload.
 GRAM_TRAFFIC_BYTES_C2 = 80.1e9
+GRAM_TRAFFIC_SOURCE = "profiles/bench_c2_gram_kernel_counters.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command; not measured in this run)"
 
 
 def log(msg):
@@ -185,9 +187,13 @@ def main():
 
     stage = np.array([[ev[k][i].elapsed_time(ev[k][i + 1]) for i in range(4)] for k in range(args.steps)])
     stage_ms = stage.mean(axis=0)
-    # fp32 MFMA Gram product: tiles on or above the diagonal only, 2 flop per multiply-add
+    # fp32 MFMA Gram product.  Algorithmic work of H += 2 X^T X with the symmetry used: the
+    # c (c + 1) / 2 distinct entries take N multiply-adds each, N c (c + 1) flop per launch; the kernel
+    # executes whole 128 x 128 tiles on or above the diagonal (the diagonal tiles compute both
+    # halves), reported next to it as flops_executed.
     T = (c + 127) // 128
-    flops = 2.0 * n * 128 * 128 * (T * (T + 1) // 2)
+    flops_executed = 2.0 * n * 128 * 128 * (T * (T + 1) // 2)
+    flops = float(n) * c * (c + 1)
     achieved = flops / (stage_ms[0] * 1e-3) / 1e12
     out = {
         "metric": "layer quantization throughput (weights/s) at 4096x4096; %MFMA / %HBM peak",
@@ -207,7 +213,11 @@ def main():
                      "achieved": achieved, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / FP32_MFMA_PEAK_TFLOPS,
                      "traffic": GRAM_TRAFFIC_BYTES_C2 if (cfg.name == "c2" and not args.tokens) else None,
-                     "flops_per_launch": flops, "ms_per_launch": float(stage_ms[0])},
+                     "traffic_source": GRAM_TRAFFIC_SOURCE if (cfg.name == "c2" and not args.tokens) else None,
+                     "algorithmic_bytes": 4.0 * n * c,
+                     "flops_per_launch": flops, "flops_executed": flops_executed,
+                     "frac_executed": flops_executed / (stage_ms[0] * 1e-3) / 1e12 / FP32_MFMA_PEAK_TFLOPS,
+                     "ms_per_launch": float(stage_ms[0])},
     }
     if not args.no_cpu_baseline:
         log("timing the float64 oracle on a bounded sample")

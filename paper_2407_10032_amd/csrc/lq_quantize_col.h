@@ -5,7 +5,7 @@
 //   * the sub-block's columns are pulled into registers with one lane per row, and the
 //     32 columns are handled in order: quantize against the row's grid (line 13 / 15),
 //     E = (w - q) / U_jj (line 16), subtract E * U[j, j+1:] inside the sub-block
-//     (line 17) with U read from LDS at wave-uniform addresses;
+//     (line 17) with U read from LDS at wave-uniform addresses, row j + 1 one column ahead;
 //   * the rest of line 17, the update of the block's later columns by the sub-block's 32
 //     error columns, is a 64 x 32 by 32 x (up to 96) product done on fp32 MFMA straight
 //     on the LDS-resident piece (the A operand is built from the per-lane errors with a
@@ -187,10 +187,25 @@ __global__ __launch_bounds__(QT) void column_block_kernel(ColArgs a, const float
     for (int kk = 0; kk < SB / 2; ++kk)
       bpre[kk] = (sb + 1 < NSB) ? ud[(cb + 2 * kk + hl) * B + (sb + 1) * SB + ml] : 0.0f;
 
+    // Row j of the sub-block's U (the same values for every lane) is fetched from LDS one
+    // column ahead: with one wavefront per SIMD nothing else hides the LDS round trip, so the
+    // reads of row j + 1 are issued before column j is quantized and are waited for only
+    // when column j + 1 needs them.
+    float ucur[SB], unxt[SB];
+    float rcur = sRinv[cb], rnxt = 0.0f;
+#pragma unroll
+    for (int jj = 1; jj < SB; ++jj) ucur[jj] = su[jj];
+
     // Columns past the end of a ragged last block hold zeros and have 1 / U_jj = 0, so
     // they produce E = 0 and change nothing; only the stores are guarded.
 #pragma unroll
     for (int j = 0; j < SB; ++j) {
+      if (j + 1 < SB) {
+        rnxt = sRinv[cb + j + 1];
+#pragma unroll
+        for (int jj = j + 2; jj < SB; ++jj) unxt[jj] = su[(j + 1) * SB + jj];
+        __builtin_amdgcn_sched_barrier(0);       // the reads stay here, ahead of the column's work
+      }
       float q;
       int code;
       const float wj = ws[j];
@@ -210,14 +225,17 @@ __global__ __launch_bounds__(QT) void column_block_kernel(ColArgs a, const float
       } else {
         quant_nu_vec(wj, g, mid, q, code);
       }
-      const float ej = (wj - q) * sRinv[cb + j];
+      const float ej = (wj - q) * rcur;
       e[j] = ej;
       ws[j] = q;
       pk[j >> 2] |= (uint32_t)code << (8 * (j & 3));
       loss = fmaf(0.5f * ej, ej, loss);
       a.Et[(int64_t)(cb + j) * a.rpad + row] = ej;      // rpad covers every lane of the launch
 #pragma unroll
-      for (int jj = j + 1; jj < SB; ++jj) ws[jj] = fmaf(-ej, su[j * SB + jj], ws[jj]);
+      for (int jj = j + 1; jj < SB; ++jj) ws[jj] = fmaf(-ej, ucur[jj], ws[jj]);
+      rcur = rnxt;
+#pragma unroll
+      for (int jj = j + 2; jj < SB; ++jj) ucur[jj] = unxt[jj];
     }
 
     // quantized values back to the LDS piece, codes to global memory
