@@ -547,18 +547,22 @@ __global__ __launch_bounds__(NTA) void affine_search_kernel(const float* __restr
 // the same tie key as the enumeration.
 template <int NTA, int BITS>
 __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restrict__ W, int64_t c,
-                                                            int64_t ldw, int g, int n2, int ngroups,
+                                                            int64_t ldw, int g, int n2, int nbk,
+                                                            int ngroups,
                                                             const double* __restrict__ om64, int T,
                                                             int t, float* __restrict__ SZ) {
   constexpr int NW = NTA / 64;
   constexpr int QM = (1 << BITS) - 1;
+  constexpr int WPAD = 16;              // +inf entries behind the sorted weights (window searches)
   extern __shared__ __align__(16) unsigned char smraw[];
   double2* sPAB = reinterpret_cast<double2*>(smraw);                         // [g + 1] prefix sums
   unsigned long long* sKey = reinterpret_cast<unsigned long long*>(sPAB + (g + 1));   // [n2]
   double* sOm = reinterpret_cast<double*>(sKey + n2);                        // [g] original order
   float* sW = reinterpret_cast<float*>(sOm + g);                             // [g] original order
-  float* sSw = sW + g;                                                       // [n2] sorted, +inf padded
+  float* sSw = sW + g;                                                       // [n2 + WPAD] sorted, +inf padded
+  uint16_t* sCnt = reinterpret_cast<uint16_t*>(sSw + n2 + WPAD);             // [nbk + 1] weights below bucket b
   __shared__ float sRed[2 * NW];
+  __shared__ int sOcc[NW];
   __shared__ double sTot[3];
   __shared__ double sBestLoss[NTA];
   __shared__ int sBestKey[NTA];
@@ -615,8 +619,28 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
       __syncthreads();
     }
   }
-  for (int i = tid; i < n2; i += NTA) sSw[i] = (i < g) ? sW[(int)(sKey[i] & 0xffffffffull)] : INFINITY;
+  for (int i = tid; i < n2 + WPAD; i += NTA) sSw[i] = (i < g) ? sW[(int)(sKey[i] & 0xffffffffull)] : INFINITY;
   __syncthreads();
+  // ---- buckets: the range [min, max] cut into nbk equal pieces; sCnt[b] = sorted weights in
+  // buckets below b.  The bucket function is monotone, so a threshold's position among the
+  // sorted weights is sCnt[its bucket] plus its position among that bucket's few weights.
+  const float bsc = (float)nbk / (hif - lof);
+  auto bucket_of = [&](float x) -> int {
+    return (int)fminf(fmaxf((x - lof) * bsc, 0.0f), (float)(nbk - 1));
+  };
+  for (int i = tid; i < g; i += NTA) {
+    const int bi = bucket_of(sSw[i]);
+    const int bp = (i > 0) ? bucket_of(sSw[i - 1]) : -1;
+    for (int b = bp + 1; b <= bi; ++b) sCnt[b] = (uint16_t)i;
+    if (i == g - 1)
+      for (int b = bi + 1; b <= nbk; ++b) sCnt[b] = (uint16_t)g;
+  }
+  __syncthreads();
+  int occ = 0;
+  for (int b = tid; b < nbk; b += NTA) occ = max(occ, (int)sCnt[b + 1] - (int)sCnt[b]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) occ = max(occ, __shfl_xor(occ, o, 64));
+  if (lane == 0) sOcc[wave] = occ;
   // ---- prefix sums of omega and omega x over the sorted group, total of omega x^2 (wavefront 0:
   // a lane takes a contiguous piece, the pieces are chained by a scan across the lanes)
   if (wave == 0) {
@@ -651,6 +675,15 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
   }
   __syncthreads();
   const double Atot = sTot[0], Btot = sTot[1], Ctot = sTot[2];
+  // window of the searches: the smallest power of two that covers the fullest bucket; beyond
+  // WPAD weights in one bucket (a group squeezed into a sliver of its range by an outlier) the
+  // search runs over the whole group
+  int occmax = sOcc[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) occmax = max(occmax, sOcc[w]);
+  const bool windowed = occmax <= WPAD;
+  int win = n2;
+  if (windowed) { win = 1; while (win < occmax) win <<= 1; }
 
   const double qmax = (double)QM;
   const double dT = (double)T;
@@ -675,14 +708,26 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
         tf = __uint_as_float(u);
       }
       thr[i] = tf;
-      pos[i] = 0;
+      pos[i] = windowed ? (int)sCnt[bucket_of(tf)] : 0;
     }
-    for (int step = n2 >> 1; step > 0; step >>= 1) {
+    // all NB reads of a step are issued before the first is used (the scheduling barrier keeps
+    // them there), so the LDS round trips of the NB searches overlap
+    for (int step = win >> 1; step > 0; step >>= 1) {
+      float v[NB];
 #pragma unroll
-      for (int i = 0; i < NB; ++i) pos[i] += (sSw[pos[i] + step - 1] < thr[i]) ? step : 0;
+      for (int i = 0; i < NB; ++i) v[i] = sSw[pos[i] + step - 1];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < NB; ++i) pos[i] += (v[i] < thr[i]) ? step : 0;
     }
+    {
+      float v[NB];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) pos[i] += (sSw[pos[i]] < thr[i]) ? 1 : 0;   // pos = weights below thr
+      for (int i = 0; i < NB; ++i) v[i] = sSw[pos[i]];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < NB; ++i) pos[i] += (v[i] < thr[i]) ? 1 : 0;       // pos = weights below thr
+    }
     // (all NB steps always run: with every index a compile-time constant the arrays stay in
     // registers; steps beyond the zero-points in use only fill entries nobody reads)
     double F = 0.0, pA = 0.0, pB = 0.0;
@@ -706,18 +751,26 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
     }
   };
 
+  // t_min R / T as the enumeration forms it; for T a power of two the product with R / T is the
+  // same number (an exact scaling), without a division per use
+  const bool tpow2 = (T & (T - 1)) == 0;
+  const double rT = R / dT;
+  auto frac_of_range = [&](int tm) -> double { return tpow2 ? (double)tm * rT : (double)tm * R / dT; };
+  // The closed form only ranks: a lane remembers its smallest value and which (s, zero-point)
+  // gave it; the tie key of the enumeration is formed once, for that candidate, afterwards.
+  int best_s = 0, best_zi = 0;
   const int rounds = (2 * t + NTA) / NTA;
   for (int rd = 0; rd < rounds; ++rd) {
     const int s = tid + rd * NTA;
     const bool live = s <= 2 * t;
     const int ta = (s > t) ? (s - t) : 0;      // smallest t_min with t_max = s - t_min <= t
     const int tb = (s < t) ? s : t;            // largest t_min
-    const double lo_a = lo0 + (double)ta * R / dT;
-    const double hi_a = hi0 - (double)(s - ta) * R / dT;
+    const double lo_a = lo0 + frac_of_range(ta);
+    const double hi_a = hi0 - frac_of_range(s - ta);
     const double S = (hi_a - lo_a) / qmax;
     const bool ok = live && (S > 0.0);
     const double Sx = ok ? S : 1.0;
-    const double lo_b = lo0 + (double)tb * R / dT;
+    const double lo_b = lo0 + frac_of_range(tb);
     const double zf = -rint(lo_a / Sx);
     const double zl = -rint(lo_b / Sx);
     double span = zf - zl;
@@ -731,23 +784,35 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
       const int cntw = min(8, nzw - z0);
       const double zb = zf - (double)z0;
       if (cntw <= 4) chunk(std::integral_constant<int, 4>{}, Sx, zb, loss);
+      else if (cntw <= 6) chunk(std::integral_constant<int, 6>{}, Sx, zb, loss);
       else chunk(std::integral_constant<int, 8>{}, Sx, zb, loss);
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
         const int zi = z0 + k;
-        if (k < cntw && zi < nz) {
-          const double Z = zf - (double)zi;
-          // first t_min of this class: smallest t_min >= ta with round(lo / S) == -Z
-          int tf = ta;
-          if (zi > 0) {
-            tf = (int)ceil(((-Z - 0.5) * S - lo0) * dT / R);
-            tf = tf < ta ? ta : (tf > tb ? tb : tf);
-          }
-          const int key = tf * (t + 1) + (s - tf);
-          if (aff_better(loss[k], key, best)) { best.loss = loss[k]; best.key = key; best.S = S; best.Z = Z; }
-        }
+        const bool take = (k < cntw) & (zi < nz) & (loss[k] < best.loss);
+        best.loss = take ? loss[k] : best.loss;
+        best.S = take ? S : best.S;
+        best_s = take ? s : best_s;
+        best_zi = take ? zi : best_zi;
       }
     }
+  }
+  if (best.loss < INFINITY) {
+    // zero-point and tie key of the lane's candidate, as the enumeration would see it: the class
+    // (s, Z) is first met at the smallest t_min >= ta with round(lo / S) == -Z
+    const int s = best_s;
+    const int ta = (s > t) ? (s - t) : 0;
+    const int tb = (s < t) ? s : t;
+    const double lo_a = lo0 + frac_of_range(ta);
+    const double zf = -rint(lo_a / best.S);
+    const double Z = zf - (double)best_zi;
+    int tf = ta;
+    if (best_zi > 0) {
+      tf = (int)ceil(((-Z - 0.5) * best.S - lo0) * dT / R);
+      tf = tf < ta ? ta : (tf > tb ? tb : tf);
+    }
+    best.Z = Z;
+    best.key = tf * (t + 1) + (s - tf);
   }
   // ---- smallest closed-form value of the workgroup; candidates within its noise are scored plainly
   sBestLoss[tid] = best.loss;
@@ -937,10 +1002,12 @@ lq_status fit_grid_impl(const float* W, int64_t r, int64_t c, int64_t ldw, const
   if (dense && g <= SORT_MAX_G) {
     int n2 = 1;
     while (n2 < g) n2 <<= 1;
-    const size_t lds_sorted = (size_t)(g + 1) * 16 + (size_t)n2 * 8 + (size_t)g * 12 + (size_t)n2 * 4;
+    const int nbk = (int)(4 * n2 < 4096 ? 4 * n2 : 4096);          // buckets of the window searches
+    const size_t lds_sorted = (size_t)(g + 1) * 16 + (size_t)n2 * 8 + (size_t)g * 12 + (size_t)(n2 + 16) * 4 +
+                              (size_t)(nbk + 2) * 2;
     static lq::DeviceOnce sorted_once;
     if (lq::DeviceOnceGuard once(sorted_once); once.first()) {
-      const int lim = (int)((SORT_MAX_G + 1) * 16 + SORT_MAX_G * 8 + SORT_MAX_G * 12 + SORT_MAX_G * 4);
+      const int lim = (int)((SORT_MAX_G + 1) * 16 + SORT_MAX_G * 8 + SORT_MAX_G * 12 + (SORT_MAX_G + 16) * 4 + 4098 * 2);
 #define LQ_ATTR(N, BT) LQ_CHECK_HIP(hipFuncSetAttribute((const void*)affine_sorted_kernel<N, BT>, \
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, lim))
       LQ_ATTR(64, 2); LQ_ATTR(64, 3); LQ_ATTR(64, 4);
@@ -950,7 +1017,7 @@ lq_status fit_grid_impl(const float* W, int64_t r, int64_t c, int64_t ldw, const
       once.done();
     }
 #define LQ_AFS(N, BT) hipLaunchKernelGGL((affine_sorted_kernel<N, BT>), ggrid, dim3(N), lds_sorted, st, W, c, ldw, \
-                                         (int)g, n2, (int)ngroups, (const double*)om64, P->T, t, grid)
+                                         (int)g, n2, nbk, (int)ngroups, (const double*)om64, P->T, t, grid)
 #define LQ_AFS_N(N) do { if (P->bits == 2) LQ_AFS(N, 2); else if (P->bits == 3) LQ_AFS(N, 3); else LQ_AFS(N, 4); } while (0)
     if (nta == 64) LQ_AFS_N(64);
     else if (nta == 128) LQ_AFS_N(128);
