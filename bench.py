@@ -185,6 +185,21 @@ def main():
         torch.cuda.synchronize()
         matvec_us = 1e3 * pe2[0].elapsed_time(pe2[1]) / 20
 
+    # the batched product (64 input vectors) on the fp32 matrix cores: apart from `value` as well
+    matmul_us = None
+    if c % 32 == 0 and (P.mode == lq.LQ_GRID_NONUNIFORM or (P.group_size or c) % 32 == 0) \
+            and packed.stride(0) % 16 == 0:
+        xb = torch.randn((64, c), dtype=torch.float32, device="cuda")
+        yb = torch.empty((64, r), dtype=torch.float32, device="cuda")
+        lq.lq_matmul_packed(packed, table, c, P, xb, yb)
+        pe3 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        pe3[0].record()
+        for _ in range(10):
+            lq.lq_matmul_packed(packed, table, c, P, xb, yb)
+        pe3[1].record()
+        torch.cuda.synchronize()
+        matmul_us = 1e3 * pe3[0].elapsed_time(pe3[1]) / 10
+
     stage = np.array([[ev[k][i].elapsed_time(ev[k][i + 1]) for i in range(4)] for k in range(args.steps)])
     stage_ms = stage.mean(axis=0)
     # fp32 MFMA Gram product.  Algorithmic work of H += 2 X^T X with the symmetry used: the
@@ -208,7 +223,10 @@ def main():
                                 "quantize_layer": stage_ms[3]},
                    # the same pass when H is reused from a projection with the same input
                    "weights_per_s_without_hessian": r * c / (float(stage_ms[1:].sum()) * 1e-3),
-                   "pack_layer_ms": pack_ms, "matvec_packed_us": matvec_us, "bits_per_weight": lq.lq_bits_per_weight(r, c, P)},
+                   "pack_layer_ms": pack_ms, "matvec_packed_us": matvec_us,
+                   "matmul_packed_nb64_us": matmul_us,
+                   "matmul_packed_nb64_tflops": (2.0 * 64 * r * c / (matmul_us * 1e-6) / 1e12) if matmul_us else None,
+                   "bits_per_weight": lq.lq_bits_per_weight(r, c, P)},
         "roofline": {"bound": "mfma", "kernel": "tn_gemm_kernel (H += 2 X^T X, upper tiles) + partial-sum reduce",
                      "achieved": achieved, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / FP32_MFMA_PEAK_TFLOPS,

@@ -133,3 +133,36 @@ def test_exact_argument_checks():
     with pytest.raises(lq.LeanQuantError):        # workspace too small
         lq.lq_quantize_exact(W, Hinv, torch.zeros((4, 16), device="cuda"), P, codes, None, None,
                              lq.alloc_workspace(256))
+
+
+@pytest.mark.parametrize("mode", ["nu", "aff"])
+def test_exact_with_a_non_finite_weight_still_walks_every_column(mode):
+    """A NaN weight has no loss error to compare, so no step would ever choose it by its score;
+    the greedy pick then falls back to the lowest index still to do.  The result for that row
+    is meaningless, but every step must pick a column not picked before (the order is a
+    permutation of 0..c-1, all codes are in range), and the other rows are untouched."""
+    lq = _lq()
+    r, c, bits = 6, 96, 3
+    W, X = _case(r, c, 6 * c, 4242)
+    H = orc.hessian(X)
+    Hinv = np.linalg.inv(orc.dampen(H, 0.01))
+    Hinv = 0.5 * (Hinv + Hinv.T)
+    d = np.diag(Hinv).copy()
+    if mode == "nu":
+        grid = orc.fit_grid_nu(W, d, bits, 4.0).astype(np.float32)
+        P = lq.lq_params_default(bits=bits)
+    else:
+        grid = orc.fit_grid_aff(W, d, bits, 4.0, group_size=0, T=64).astype(np.float32)
+        P = lq.lq_params_default(bits=bits, mode=lq.LQ_GRID_AFFINE, T=64)
+    Hd = hx.to_dev(Hinv, torch.float64)
+    _, codes_ok, order_ok, _ = _run_exact(lq, W, Hd, grid, P)
+    Wbad = W.copy()
+    Wbad[2, 17] = np.nan
+    Wq, codes, order, _ = _run_exact(lq, Wbad, Hd, grid, P)
+    for k in range(r):
+        assert sorted(order[k].tolist()) == list(range(c)), k
+    assert codes.max() < (1 << bits)
+    keep = [k for k in range(r) if k != 2]
+    np.testing.assert_array_equal(codes[keep], codes_ok[keep])
+    np.testing.assert_array_equal(order[keep], order_ok[keep])
+    assert np.all(np.isfinite(Wq[keep]))
