@@ -57,8 +57,9 @@ __device__ __forceinline__ int xcd_swizzle(int b, int total) {
   return (slot / XCD_CHUNK) * group + xcd * XCD_CHUNK + (slot % XCD_CHUNK);
 }
 
-// Patch-major enumeration of a tiles_m x tiles_n grid (general) or of its upper triangle
-// (SYM, tiles_m == tiles_n): index -> (bi, bj).  Walks the patches in row-major order.
+// Patch-major enumeration of a tiles_m x tiles_n grid (general) or of the tiles strictly above
+// the diagonal of a square grid (SYM, tiles_m == tiles_n): index -> (bi, bj).  Walks the
+// patches in row-major order.
 template <bool SYM>
 __device__ __forceinline__ void decode_patch_major(int idx, int tiles_m, int tiles_n, int& bi, int& bj) {
   const int pm = (tiles_m + PATCH - 1) / PATCH, pn = (tiles_n + PATCH - 1) / PATCH;
@@ -66,11 +67,12 @@ __device__ __forceinline__ void decode_patch_major(int idx, int tiles_m, int til
     const int h = min(PATCH, tiles_m - pi * PATCH);
     for (int pj = SYM ? pi : 0; pj < pn; ++pj) {
       const int w = min(PATCH, tiles_n - pj * PATCH);
-      const int cnt = (SYM && pi == pj) ? h * (h + 1) / 2 : h * w;
+      const int cnt = (SYM && pi == pj) ? h * (h - 1) / 2 : h * w;
       if (idx < cnt) {
         int li, lj;
         if (SYM && pi == pj) {
-          decode_upper(idx, h, li, lj);
+          decode_upper(idx, h - 1, li, lj);   // strictly upper of h x h = upper with diagonal of (h - 1) x (h - 1), shifted
+          lj += 1;
         } else {
           li = idx / w;
           lj = idx - li * w;
@@ -83,6 +85,14 @@ __device__ __forceinline__ void decode_patch_major(int idx, int tiles_m, int til
     }
   }
   bi = 0; bj = 0;  // not reached for idx < number of tiles
+}
+
+// Tile ids of a symmetric product with T x T tiles: the T (T - 1) / 2 tiles above the diagonal
+// in patch-major order, then the T diagonal tiles.
+__device__ __forceinline__ void decode_sym_tile(int tile, int T, int& bi, int& bj) {
+  const int above = T * (T - 1) / 2;
+  if (tile >= above) { bi = bj = tile - above; return; }
+  decode_patch_major<true>(tile, T, T, bi, bj);
 }
 
 // One k-chunk (KT rows x 128 columns) of an operand in registers: KT / 8 float4 per thread,
@@ -236,8 +246,9 @@ __device__ __forceinline__ void tn_store_chunk_at(float* __restrict__ d, const C
 
 // One k stage of tn_mainloop_fast over buffer `cur`.  On entry o.*[0] holds the operands
 // of k-step 0 of this stage; if MORE, on exit it holds those of k-step 0 of the next
-// stage, whose data (rp, rq) this stage stores to buffer `nxt`.
-template <int KT, bool MORE, bool DIAG>
+// stage, whose data (rp, rq) this stage stores to buffer `nxt`.  MASK: which of the wave's four
+// sub-tiles are computed (bit 2 tm + tn); operands that no computed sub-tile uses are not read.
+template <int KT, bool MORE, bool DIAG, int MASK>
 __device__ __forceinline__ void tn_fast_stage(const TnLdsAddr& cur, const TnLdsAddr& nxt,
                                               const ChunkRegs<KT>& rp, const ChunkRegs<KT>& rq,
                                               TnOperands& o, Acc2x2& acc) {
@@ -266,10 +277,10 @@ __device__ __forceinline__ void tn_fast_stage(const TnLdsAddr& cur, const TnLdsA
       o.b0[n] = nxt.q[0]; o.b1[n] = nxt.q[64];
     }
     __builtin_amdgcn_sched_barrier(0);
-    acc.t[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a0[c], o.b0[c], acc.t[0][0], 0, 0, 0);
-    acc.t[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a0[c], o.b1[c], acc.t[0][1], 0, 0, 0);
-    acc.t[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a1[c], o.b0[c], acc.t[1][0], 0, 0, 0);
-    acc.t[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a1[c], o.b1[c], acc.t[1][1], 0, 0, 0);
+    if constexpr (MASK & 1) acc.t[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a0[c], o.b0[c], acc.t[0][0], 0, 0, 0);
+    if constexpr (MASK & 2) acc.t[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a0[c], o.b1[c], acc.t[0][1], 0, 0, 0);
+    if constexpr (MASK & 4) acc.t[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a1[c], o.b0[c], acc.t[1][0], 0, 0, 0);
+    if constexpr (MASK & 8) acc.t[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a1[c], o.b1[c], acc.t[1][1], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
   }
 }
@@ -286,7 +297,7 @@ __device__ __forceinline__ void tn_fast_stage(const TnLdsAddr& cur, const TnLdsA
 //     the two buffers, so that a stage has no vector-ALU instruction at all: a VALU
 //     instruction between MFMAs was measured to idle the MFMA pipe for about 16 cycles.
 // Scheduling barriers pin the order.  nst = number of stages (>= 1), wave-uniform.
-template <int KT, bool DIAG>
+template <int KT, bool DIAG, int MASK>
 __device__ __forceinline__ void tn_fast_loop(TnFastSrc<KT>& sp, TnFastSrc<KT>& sq, int nst,
                                              const TnLdsAddr& b0, const TnLdsAddr& b1,
                                              ChunkRegs<KT>& rp, ChunkRegs<KT>& rq, TnOperands& o,
@@ -295,19 +306,19 @@ __device__ __forceinline__ void tn_fast_loop(TnFastSrc<KT>& sp, TnFastSrc<KT>& s
   while (left >= 2) {
     sp.next(); rp = sp.load();
     if (!DIAG) { sq.next(); rq = sq.load(); }
-    tn_fast_stage<KT, true, DIAG>(b0, b1, rp, rq, o, acc);
+    tn_fast_stage<KT, true, DIAG, MASK>(b0, b1, rp, rq, o, acc);
     sp.next(); rp = sp.load();
     if (!DIAG) { sq.next(); rq = sq.load(); }
-    tn_fast_stage<KT, true, DIAG>(b1, b0, rp, rq, o, acc);
+    tn_fast_stage<KT, true, DIAG, MASK>(b1, b0, rp, rq, o, acc);
     left -= 2;
   }
   if (left) {
     sp.next(); rp = sp.load();
     if (!DIAG) { sq.next(); rq = sq.load(); }
-    tn_fast_stage<KT, true, DIAG>(b0, b1, rp, rq, o, acc);
-    tn_fast_stage<KT, false, DIAG>(b1, b1, rp, rq, o, acc);
+    tn_fast_stage<KT, true, DIAG, MASK>(b0, b1, rp, rq, o, acc);
+    tn_fast_stage<KT, false, DIAG, MASK>(b1, b1, rp, rq, o, acc);
   } else {
-    tn_fast_stage<KT, false, DIAG>(b0, b0, rp, rq, o, acc);
+    tn_fast_stage<KT, false, DIAG, MASK>(b0, b0, rp, rq, o, acc);
   }
 }
 
@@ -338,22 +349,47 @@ __device__ __forceinline__ void tn_mainloop_fast(const TnGemmArgs& a, float* sme
   TnOperands o;
   o.a0[0] = b0.p[0]; o.a1[0] = b0.p[64];
   o.b0[0] = b0.q[0]; o.b1[0] = b0.q[64];
-  if (diag) tn_fast_loop<KT, true>(sp, sq, nst, b0, b1, rp, rq, o, acc);
-  else tn_fast_loop<KT, false>(sp, sq, nst, b0, b1, rp, rq, o, acc);
+  // A diagonal tile of a symmetric product is needed on and above its own diagonal only: of
+  // the 4 x 4 sub-tiles (wm + 2 tm, wn + 2 tn) the six with a row index above the column index
+  // are left at zero (the reduce kernel mirrors their transposes): wavefront (1, 0) keeps
+  // sub-tile (1, 2) alone, the other three drop (wm + 2, wn).
+  if (diag) {
+    if (wm * 2 + wn == 2) tn_fast_loop<KT, true, 2>(sp, sq, nst, b0, b1, rp, rq, o, acc);
+    else tn_fast_loop<KT, true, 11>(sp, sq, nst, b0, b1, rp, rq, o, acc);
+  } else {
+    tn_fast_loop<KT, false, 15>(sp, sq, nst, b0, b1, rp, rq, o, acc);
+  }
 }
 
 template <int KT, bool SYM, bool PARTIAL, bool VEC, int MINW = 2>
 __global__ __launch_bounds__(WG_THREADS, MINW) void tn_gemm_kernel(TnGemmArgs a) {
   extern __shared__ __align__(16) float smem[];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: lives in a scalar register
   const int wm = wave >> 1, wn = wave & 1;
 
   const int work = xcd_swizzle(blockIdx.x, a.splits * a.ntiles);
-  const int split = work / a.ntiles;
-  const int tile = work - split * a.ntiles;
-  int bi, bj;
-  decode_patch_major<SYM>(tile, a.tiles_m, a.tiles_n, bi, bj);
+  int split, tile, bi, bj;
+  if (SYM) {
+    // Diagonal tiles do less work (see tn_mainloop_fast) and finish earlier.  Workgroups that
+    // share operand panels in an XCD's L2 stay together only while they take the same time,
+    // so all (slice, diagonal tile) items come after all items of the tiles above the diagonal.
+    const int above = a.ntiles - a.tiles_m;
+    if (work < a.splits * above) {
+      split = work / above;
+      tile = work - split * above;
+    } else {
+      const int w = work - a.splits * above;
+      split = w / a.tiles_m;
+      tile = above + (w - split * a.tiles_m);
+    }
+    decode_sym_tile(tile, a.tiles_m, bi, bj);
+  } else {
+    split = work / a.ntiles;
+    tile = work - split * a.ntiles;
+    decode_patch_major<false>(tile, a.tiles_m, a.tiles_n, bi, bj);
+  }
   const bool diag = SYM && (bi == bj);
   const int64_t m0 = (int64_t)bi * TILE, n0 = (int64_t)bj * TILE;
   const int64_t kbeg = (int64_t)split * a.k_per_split;
@@ -520,6 +556,9 @@ __global__ __launch_bounds__(WG_THREADS) void tn_small_kernel(TnGemmArgs a) {
 
 // Sum the token-split partial tiles in split order and add alpha * sum to C, writing
 // the tile at (bi, bj) and its transpose at (bj, bi).  Four workgroups per upper tile.
+// Of a diagonal tile only the 32 x 32 sub-tiles on and above the diagonal are taken from the
+// partial sums (the product kernel may leave the others at zero); the sub-tiles below are the
+// transposes of those above.
 static __global__ __launch_bounds__(WG_THREADS) void tn_reduce_sym_kernel(const float* __restrict__ partial,
                                                                   int splits, int ntiles, int T,
                                                                   float* __restrict__ C, int64_t ldc,
@@ -528,7 +567,7 @@ static __global__ __launch_bounds__(WG_THREADS) void tn_reduce_sym_kernel(const 
   const int tid = threadIdx.x;
   const int tile = blockIdx.x >> 2;        // four workgroups per tile, 32 rows each
   int bi, bj;
-  decode_patch_major<true>(tile, T, T, bi, bj);
+  decode_sym_tile(tile, T, bi, bj);
   const int64_t m0 = (int64_t)bi * TILE, n0 = (int64_t)bj * TILE;
   const bool vecc = (ldc % 4 == 0) && ((reinterpret_cast<uintptr_t>(C) & 15) == 0);
   {
@@ -549,7 +588,7 @@ static __global__ __launch_bounds__(WG_THREADS) void tn_reduce_sym_kernel(const 
       s.x *= alpha; s.y *= alpha; s.z *= alpha; s.w *= alpha;
       int64_t row = m0 + sb * 32 + lr;
       int64_t col = n0 + 4 * c4;
-      if (row < M) {
+      if (row < M && (bi != bj || 4 * c4 >= sb * 32)) {
         float* dst = C + row * ldc + col;
         if (vecc && col + 3 < M) {
           float4 o = *reinterpret_cast<const float4*>(dst);
@@ -566,22 +605,25 @@ static __global__ __launch_bounds__(WG_THREADS) void tn_reduce_sym_kernel(const 
       d[0] = s.x; d[1] = s.y; d[2] = s.z; d[3] = s.w;
     }
     __syncthreads();
-    if (bi != bj) {
+    {
       // transpose: target row n0 + lc, target columns m0 + sb*32 + (0..31); the sixteen old
-      // values of a thread are loaded before its first store
+      // values of a thread are loaded before its first store.  Diagonal tile: only the
+      // columns lc of the sub-tiles to the right of sub-tile (sb, sb).
+      const int lc_min = (bi != bj) ? 0 : (sb + 1) * 32;
       const int lr = tid & 31;
       const int64_t col = m0 + sb * 32 + lr;
       float oldv[TILE / 8];
 #pragma unroll
       for (int q = 0; q < TILE / 8; ++q) {
-        const int64_t row = n0 + (tid >> 5) + 8 * q;
-        oldv[q] = (row < M && col < M) ? C[row * ldc + col] : 0.0f;
+        const int lc = (tid >> 5) + 8 * q;
+        const int64_t row = n0 + lc;
+        oldv[q] = (lc >= lc_min && row < M && col < M) ? C[row * ldc + col] : 0.0f;
       }
 #pragma unroll
       for (int q = 0; q < TILE / 8; ++q) {
         const int lc = (tid >> 5) + 8 * q;
         const int64_t row = n0 + lc;
-        if (row < M && col < M) C[row * ldc + col] = oldv[q] + st[lr * 129 + lc];
+        if (lc >= lc_min && row < M && col < M) C[row * ldc + col] = oldv[q] + st[lr * 129 + lc];
       }
     }
     __syncthreads();
