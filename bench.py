@@ -204,10 +204,11 @@ def main():
     stage_ms = stage.mean(axis=0)
     # fp32 MFMA Gram product.  Algorithmic work of H += 2 X^T X with the symmetry used: the
     # c (c + 1) / 2 distinct entries take N multiply-adds each, N c (c + 1) flop per launch; the kernel
-    # executes whole 128 x 128 tiles on or above the diagonal (the diagonal tiles compute both
-    # halves), reported next to it as flops_executed.
+    # executes whole 128 x 128 tiles above the diagonal and, of a diagonal tile, the ten 32 x 32
+    # sub-tiles on and above the diagonal (four of them compute both halves), reported next to it
+    # as flops_executed.
     T = (c + 127) // 128
-    flops_executed = 2.0 * n * 128 * 128 * (T * (T + 1) // 2)
+    flops_executed = 2.0 * n * (128 * 128 * (T * (T - 1) // 2) + 10 * 32 * 32 * T)
     flops = float(n) * c * (c + 1)
     achieved = flops / (stage_ms[0] * 1e-3) / 1e12
     out = {

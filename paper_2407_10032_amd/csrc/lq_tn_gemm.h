@@ -499,6 +499,17 @@ __global__ __launch_bounds__(WG_THREADS) void tn_small_kernel(TnGemmArgs a) {
   const int K = (int)a.K;                    // <= 128, even
 
   const bool inner = VEC && (m0 + ST <= a.M) && (n0 + ST <= a.N);
+  // The old values of C are fetched together with the operands (their latency passes under the
+  // operands' and the MFMA loop) and all sixteen before the first store (a load after a store to a possibly aliasing
+  // address would wait for it).
+  const int64_t col = n0 + wn * 32 + ml;
+  float oldv[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int64_t row = m0 + wm * 32 + 8 * (v >> 2) + 4 * kl + (v & 3);
+    oldv[v] = (row < a.M && col < a.N) ? a.C[row * a.ldc + col] : 0.0f;
+  }
+
   {
     // 128 rows x 16 float4 per operand = 8 per thread and operand, all in flight together
     constexpr int PER = 128 * (ST / 4) / WG_THREADS;
@@ -538,15 +549,6 @@ __global__ __launch_bounds__(WG_THREADS) void tn_small_kernel(TnGemmArgs a) {
   for (int k = 0; k < 128; k += 2)
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pp[k * ST], pq[k * ST], acc, 0, 0, 0);
 
-  // all sixteen old values are loaded before the first store (a load after a store to a
-  // possibly aliasing address would wait for it)
-  const int64_t col = n0 + wn * 32 + ml;
-  float oldv[16];
-#pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int64_t row = m0 + wm * 32 + 8 * (v >> 2) + 4 * kl + (v & 3);
-    oldv[v] = (row < a.M && col < a.N) ? a.C[row * a.ldc + col] : 0.0f;
-  }
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int64_t row = m0 + wm * 32 + 8 * (v >> 2) + 4 * kl + (v & 3);
