@@ -222,3 +222,43 @@ def test_matmul_from_the_stored_form(mode, bits, group, r, c, nb):
         lq.lq_matvec_packed(packed, table, c, P, hx.to_dev(X), Y1)
         torch.cuda.synchronize()
         assert np.all(np.abs(got - Y1.cpu().numpy()) <= 4e-6 * scale + 1e-30)
+
+
+@pytest.mark.parametrize("mode,bits,group,r,c,nb", [("nu", 3, 0, 53248, 16384, 96), ("aff", 4, 128, 28672, 8192, 256),
+                                                    ("aff", 2, 64, 53248, 16384, 40)])
+def test_matmul_at_the_size_of_the_large_layers(mode, bits, group, r, c, nb):
+    """The batched product at the row and column counts of configurations 4 and 5 (several hundred
+    row tiles, batches that end inside a tile).  Seeded codes and tables; the library packs and
+    multiplies the whole layer, the oracle packs and multiplies sampled rows (first and last tile
+    included) from the same seeded codes."""
+    lq = _lq()
+    rng = np.random.default_rng(7 + bits + nb)
+    K = 1 << bits
+    codes = rng.integers(0, K, size=(r, c), dtype=np.uint8)
+    if mode == "nu":
+        grid = np.sort(rng.normal(0, 0.02, size=(r, K)), axis=1).astype(np.float32)
+        P = lq.lq_params_default(bits=bits, mode=lq.LQ_GRID_NONUNIFORM)
+    else:
+        ng = c // group
+        S = (rng.random((r, ng)) * 0.01 + 1e-3)
+        Z = rng.integers(-3, K + 3, size=(r, ng)).astype(np.float64)
+        grid = np.stack([S, Z], axis=-1).astype(np.float32)
+        P = lq.lq_params_default(bits=bits, mode=lq.LQ_GRID_AFFINE, group_size=group)
+    rb = lq.lq_packed_row_bytes(c, bits)
+    packed = torch.zeros((r, rb), dtype=torch.uint8, device="cuda")
+    table = torch.empty(grid.size, dtype=torch.int16, device="cuda")
+    lq.lq_pack_layer(hx.to_dev(codes, torch.uint8), hx.to_dev(grid), P, packed, table)
+    X = rng.standard_normal((nb, c)).astype(np.float32)
+    Y = torch.full((nb, r), float("nan"), device="cuda")
+    lq.lq_matmul_packed(packed, table, c, P, hx.to_dev(X), Y)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(Y).all())
+    rows = np.unique(np.concatenate([np.arange(0, 3), np.arange(r - 3, r), rng.integers(0, r, size=26)]))
+    exp_packed = po.pack_codes(codes[rows], bits)
+    exp_table = po.table_nu(grid[rows]) if mode == "nu" else po.table_aff(grid[rows])
+    ref = po.matvec_packed(exp_packed, exp_table, X, c, bits, mode, group)          # [nb x rows]
+    Wh = po.dequantize(exp_packed, exp_table, c, bits, mode, group).astype(np.float64)
+    scale = np.abs(X.astype(np.float64)) @ np.abs(Wh).T
+    got = Y[:, torch.as_tensor(rows, device="cuda")].cpu().numpy()
+    err = np.abs(got - ref)
+    assert np.all(err <= 4e-6 * scale + 1e-30), float(np.max(err / (scale + 1e-30)))
