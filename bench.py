@@ -29,7 +29,7 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 # cannot read hardware counters).  It is the figure of the two rocprofv3 --pmc runs of this very
 # command (FETCH_SIZE, then WRITE_SIZE, each scaled by a plain copy of known size) that
 # profiles/bench_c2_gram_kernel_counters.md summarises; only valid for that workload.
-GRAM_TRAFFIC_BYTES_C2 = 48.4e9
+GRAM_TRAFFIC_BYTES_C2 = 48.1e9
 GRAM_TRAFFIC_SOURCE = "profiles/bench_c2_gram_kernel_counters.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command; not measured in this run)"
 
 
