@@ -78,6 +78,28 @@ def test_cholesky_inv_matches_oracle(c, n):
     assert np.max(np.abs(resid)) < 5e-4
 
 
+def test_cholesky_inv_at_fifty_block_columns():
+    """c = 6400 (50 block columns, past the switch from the single-shot to the streaming panel
+    kernel, trailing updates of more than a thousand tiles); same bars as above."""
+    c, n = 6400, 8192
+    _say(f"cholesky c={c}")
+    X = _layer(c, n, 200 + c)
+    Href = orc.hessian(X)
+    H32 = Href.astype(np.float32)
+    U, d, info = hx.gpu_cholesky(hx.to_dev(H32), 0.01)
+    assert info == 0
+    U = U.cpu().numpy().astype(np.float64)
+    d = d.cpu().numpy().astype(np.float64)
+    Uref, dref = orc.cholesky_inv(H32.astype(np.float64), 0.01)
+    assert np.array_equal(U, np.triu(U))
+    assert np.max(np.abs(U - Uref) / np.sqrt(dref)[None, :]) < 2e-5
+    assert np.max(np.abs(d - dref) / dref) < 2e-5
+    Hd = orc.dampen(H32.astype(np.float64), 0.01)
+    cols = np.array([0, 1, 127, 128, 511, 512, 3000, c - 129, c - 1])
+    resid = U.T @ (U @ Hd[:, cols]) - np.eye(c)[:, cols]
+    assert np.max(np.abs(resid)) < 5e-4
+
+
 def test_cholesky_reports_not_positive_definite():
     _say("cholesky not PD")
     c = 130
