@@ -30,7 +30,10 @@ def _layer(c, n, seed, outliers=4, scale=20.0):
 
 # ------------------------------------------------------------------ A: Hessian
 @pytest.mark.parametrize("c,n,chunks", [(128, 64, 1), (200, 777, 1), (512, 2048, 1), (300, 1500, 3),
-                                        (1, 40, 1), (131, 1, 1)])
+                                        (1, 40, 1), (131, 1, 1),
+                                        # 9 and 17 tile rows: the last patch of the tile order is a single
+                                        # diagonal tile; 1152 = 9 whole tiles takes the unguarded loop
+                                        (1100, 320, 1), (1152, 4096, 2), (2100, 512, 1)])
 def test_hessian_matches_oracle(c, n, chunks):
     _say(f"hessian c={c} n={n} chunks={chunks}")
     X = _layer(c, n, 100 + c + n)
