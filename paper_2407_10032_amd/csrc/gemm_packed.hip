@@ -284,14 +284,16 @@ constexpr size_t rows32_lds() {
   return (size_t)(4 * (32 * LDT + 32 * MT * LDT) + (AFF ? 0 : 32 * (1 << BITS))) * sizeof(float);
 }
 
-// fewer 128-row workgroups than this: the 32-row kernel fills the chip better
+// fewer 128-row workgroups than this: the 32-row kernel fills the chip better (measured: for up
+// to 32 vectors it still leads at 224 workgroups, for 64 it no longer does)
 constexpr int64_t ROWS32_BELOW = 192;
+constexpr int64_t ROWS32_BELOW_SMALL_BATCH = 320;
 
 template <int BITS, bool AFF>
 lq_status launch_mm(const MmArgs& a, hipStream_t st) {
   const unsigned gx = (unsigned)lq::ceil_div(a.r, WROWS);
   const int64_t vt = a.nb <= 32 ? 32 : 64;
-  if ((int64_t)gx * lq::ceil_div(a.nb, vt) < ROWS32_BELOW) {
+  if ((int64_t)gx * lq::ceil_div(a.nb, vt) < (a.nb <= 32 ? ROWS32_BELOW_SMALL_BATCH : ROWS32_BELOW)) {
     static lq::DeviceOnce attr_once;
     if (lq::DeviceOnceGuard once(attr_once); once.first()) {
       LQ_CHECK_HIP(hipFuncSetAttribute((const void*)matmul_packed_rows32_kernel<BITS, AFF, 1>,

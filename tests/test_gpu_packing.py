@@ -179,12 +179,13 @@ def test_matvec_from_the_stored_form(mode, bits, group, r, c, nb):
                                              ("aff", 4, 128), ("aff", 2, 64), ("aff", 3, 0)])
 @pytest.mark.parametrize("r,c,nb", [(37, 1024, 16), (200, 4096, 33), (130, 2048, 64), (64, 11008, 40),
                                     (257, 160, 17), (16, 16384, 32), (300, 4128, 100), (5, 32, 1),
-                                    (24613, 64, 64), (12330, 96, 100), (24700, 32, 7)])
+                                    (24613, 64, 64), (12330, 96, 100), (41003, 32, 7)])
 def test_matmul_from_the_stored_form(mode, bits, group, r, c, nb):
     """The batched (matrix-core) product with a stored layer against the float64 oracle, at the
     tolerance of the one-vector product: ragged row counts (tiles of 32 and of 128), batches that are not
     multiples of 32 / 64, column counts that are not multiples of the 64-column stage.  The library
-    picks its kernel by the number of 128-row workgroups (below 192: the 32-row kernel); the last three
+    picks its kernel by the number of 128-row workgroups (below 192, or 320 for up to 32 vectors: the
+    32-row kernel); the last three
     shapes have enough rows for the 128-row kernel and end inside a tile."""
     lq = _lq()
     if mode == "aff" and group and c % group:
