@@ -783,7 +783,9 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
       double loss[8];
       const int cntw = min(8, nzw - z0);
       const double zb = zf - (double)z0;
-      if (cntw <= 4) chunk(std::integral_constant<int, 4>{}, Sx, zb, loss);
+      if (cntw <= 2) chunk(std::integral_constant<int, 2>{}, Sx, zb, loss);
+      else if (cntw <= 3) chunk(std::integral_constant<int, 3>{}, Sx, zb, loss);
+      else if (cntw <= 4) chunk(std::integral_constant<int, 4>{}, Sx, zb, loss);
       else if (cntw <= 6) chunk(std::integral_constant<int, 6>{}, Sx, zb, loss);
       else chunk(std::integral_constant<int, 8>{}, Sx, zb, loss);
 #pragma unroll
