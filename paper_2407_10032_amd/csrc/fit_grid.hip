@@ -528,6 +528,43 @@ __global__ __launch_bounds__(NTA) void affine_search_kernel(const float* __restr
   if (tid == 0) { out[0] = (float)sBestS[0]; out[1] = (float)sBestZ[0]; }
 }
 
+// double -> float rounded towards +infinity (the smallest float >= x), for 8, 4, 2 or 1 values.  The
+// rounding mode of single-precision results (MODE bits 1:0, which v_cvt_f32_f64 follows) is
+// switched inside the statement and back, so no other instruction ever runs under it; the waits
+// keep the switch clear of the vector instructions issued before and after it.
+#define LQ_RU_ON  "s_nop 3\n\ts_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 1\n\ts_nop 2\n\t"
+#define LQ_RU_OFF "s_nop 2\n\ts_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 0\n\ts_nop 1"
+__device__ __forceinline__ void cvt_up4(float* o, const double* a) {
+  asm volatile(LQ_RU_ON "v_cvt_f32_f64 %0, %4\n\tv_cvt_f32_f64 %1, %5\n\tv_cvt_f32_f64 %2, %6\n\tv_cvt_f32_f64 %3, %7\n\t" LQ_RU_OFF
+               : "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]), "=&v"(o[3])
+               : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]));
+}
+__device__ __forceinline__ void cvt_up8(float* o, const double* a) {
+  asm volatile(LQ_RU_ON "v_cvt_f32_f64 %0, %8\n\tv_cvt_f32_f64 %1, %9\n\tv_cvt_f32_f64 %2, %10\n\tv_cvt_f32_f64 %3, %11\n\t"
+               "v_cvt_f32_f64 %4, %12\n\tv_cvt_f32_f64 %5, %13\n\tv_cvt_f32_f64 %6, %14\n\tv_cvt_f32_f64 %7, %15\n\t" LQ_RU_OFF
+               : "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]), "=&v"(o[3]), "=&v"(o[4]), "=&v"(o[5]), "=&v"(o[6]), "=&v"(o[7])
+               : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]));
+}
+__device__ __forceinline__ void cvt_up2(float* o, const double* a) {
+  asm volatile(LQ_RU_ON "v_cvt_f32_f64 %0, %2\n\tv_cvt_f32_f64 %1, %3\n\t" LQ_RU_OFF
+               : "=&v"(o[0]), "=&v"(o[1]) : "v"(a[0]), "v"(a[1]));
+}
+__device__ __forceinline__ void cvt_up1(float* o, const double* a) {
+  asm volatile(LQ_RU_ON "v_cvt_f32_f64 %0, %1\n\t" LQ_RU_OFF : "=&v"(o[0]) : "v"(a[0]));
+}
+#undef LQ_RU_ON
+#undef LQ_RU_OFF
+template <int N>
+__device__ __forceinline__ void cvt_up(float (&o)[N], const double (&a)[N]) {
+  constexpr int N8 = N / 8 * 8;
+  constexpr int N4 = N / 4 * 4;
+#pragma unroll
+  for (int i = 0; i < N8; i += 8) cvt_up8(&o[i], &a[i]);
+  if constexpr (N4 > N8) cvt_up4(&o[N8], &a[N8]);
+  if constexpr (N - N4 >= 2) cvt_up2(&o[N4], &a[N4]);
+  if constexpr ((N - N4) % 2 == 1) cvt_up1(&o[N - 1], &a[N - 1]);
+}
+
 // ------------------------------------------------------------ affine: search on a sorted group
 // The same search (distinct (s, Z) classes, same keys, same minimizer) with the cost of a
 // candidate made independent of the group size.  The group is sorted once.  For a scale S the
@@ -698,18 +735,16 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
     const double jmin = -zb;                      // lowest level of the chunk
     float thr[NB];
     int pos[NB];
+    {
+      // thresholds (j + 1/2) S as the smallest floats not below them: w < threshold exactly when
+      // w < that float
+      double td[NB];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      const double td = (jmin + (double)i + 0.5) * S;
-      float tf = (float)td;
-      if ((double)tf < td) {                      // smallest float >= td: w < td exactly when w < tf
-        uint32_t u = __float_as_uint(tf);
-        u = (tf >= 0.0f) ? (((u & 0x7fffffffu) == 0u) ? 1u : u + 1u) : u - 1u;
-        tf = __uint_as_float(u);
-      }
-      thr[i] = tf;
-      pos[i] = windowed ? (int)sCnt[bucket_of(tf)] : 0;
+      for (int i = 0; i < NB; ++i) td[i] = (jmin + (double)i + 0.5) * S;
+      cvt_up<NB>(thr, td);
     }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) pos[i] = windowed ? (int)sCnt[bucket_of(thr[i])] : 0;
     // all NB reads of a step are issued before the first is used (the scheduling barrier keeps
     // them there), so the LDS round trips of the NB searches overlap
     for (int step = win >> 1; step > 0; step >>= 1) {
