@@ -163,3 +163,13 @@ def test_argument_errors_of_the_calls_beyond_the_pass(lib):
     # lq_hinv_from_factor(U, ldu, c, Hinv, ldh, stream)
     _bad(lib.lq_hinv_from_factor(None, 8, 8, d, 8, None), "null")
     assert lib.lq_hinv_from_factor(d, 4, 8, d, 8, None) == lq.LQ_ERR_INVALID_ARG
+
+
+def test_bench_refuses_more_than_one_gpu(repo_root):
+    """The path is built for one GPU: asked for more, bench.py says so and runs nothing."""
+    import subprocess
+    import sys
+    p = subprocess.run([sys.executable, os.path.join(repo_root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert p.returncode != 0
+    assert "one GPU" in p.stderr and p.stdout.strip() == ""
