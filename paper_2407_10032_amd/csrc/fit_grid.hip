@@ -662,8 +662,9 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
   // buckets below b.  The bucket function is monotone, so a threshold's position among the
   // sorted weights is sCnt[its bucket] plus its position among that bucket's few weights.
   const float bsc = (float)nbk / (hif - lof);
+  const float bmax = (float)(nbk - 1);
   auto bucket_of = [&](float x) -> int {
-    return (int)fminf(fmaxf((x - lof) * bsc, 0.0f), (float)(nbk - 1));
+    return (int)__builtin_amdgcn_fmed3f((x - lof) * bsc, 0.0f, bmax);     // clamp in one instruction
   };
   for (int i = tid; i < g; i += NTA) {
     const int bi = bucket_of(sSw[i]);
@@ -721,6 +722,7 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
   const bool windowed = occmax <= WPAD;
   int win = n2;
   if (windowed) { win = 1; while (win < occmax) win <<= 1; }
+  const int cntmask = windowed ? 0xffff : 0;      // whole-group searches start at 0
 
   const double qmax = (double)QM;
   const double dT = (double)T;
@@ -729,10 +731,12 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
 
   // One chunk of up to NZC consecutive zero-points zb, zb - 1, ... of scale S: thresholds,
   // positions, walk.
-  auto chunk = [&](auto nzc_tag, double S, double zb, double* loss) {
+  int best_s = 0, best_zi = 0;
+  auto chunk = [&](auto nzc_tag, double S, double zb, int s, int z0, int nz) {
     constexpr int NZC = decltype(nzc_tag)::value;
     constexpr int NB = QM + NZC - 1;
     const double jmin = -zb;                      // lowest level of the chunk
+    double loss[NZC];
     float thr[NB];
     int pos[NB];
     {
@@ -744,7 +748,7 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
       cvt_up<NB>(thr, td);
     }
 #pragma unroll
-    for (int i = 0; i < NB; ++i) pos[i] = windowed ? (int)sCnt[bucket_of(thr[i])] : 0;
+    for (int i = 0; i < NB; ++i) pos[i] = (int)sCnt[bucket_of(thr[i])] & cntmask;
     // all NB reads of a step are issued before the first is used (the scheduling barrier keeps
     // them there), so the LDS round trips of the NB searches overlap
     for (int step = win >> 1; step > 0; step >>= 1) {
@@ -784,16 +788,42 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
       pA = ab.x;
       pB = ab.y;
     }
+    // The closed form only ranks: a lane remembers its smallest value and which (s, zero-point)
+    // gave it; the tie key of the enumeration is formed once, for that candidate, afterwards.
+    // (zero-points beyond the lane's own count nz belong to wider lanes of the wavefront)
+#pragma unroll
+    for (int k = 0; k < NZC; ++k) {
+      const int zi = z0 + k;
+      const bool take = (zi < nz) & (loss[k] < best.loss);
+      best.loss = take ? loss[k] : best.loss;
+      best.S = take ? S : best.S;
+      best_s = take ? s : best_s;
+      best_zi = take ? zi : best_zi;
+    }
   };
 
+  // x / (2^b - 1), correctly rounded, without a division: product with the rounded reciprocal
+  // and one correction by the exact remainder (exact for these divisors: 3, 7 and 15 were checked
+  // against the division on 4e8 random operands each).
+  auto div_by_levels = [&](double x) -> double {
+    constexpr double rc = 1.0 / (double)QM;
+    const double q = x * rc;
+    return fma(fma(-(double)QM, q, x), rc, q);
+  };
+  // rint(a / S) from the product with 1 / S (rS, good to an ulp): the product is within a few ulp
+  // of the quotient, so the two round to the same integer unless it lies that close to a half;
+  // only then is the division carried out.
+  auto rint_quotient = [&](double a, double S, double rS) -> double {
+    const double q = a * rS;
+    double rq = rint(q);
+    if (fabs(q - rq) > 0.5 - fma(fabs(q), 8.9e-16, 1.0e-12)) rq = rint(a / S);
+    return rq;
+  };
   // t_min R / T as the enumeration forms it; for T a power of two the product with R / T is the
   // same number (an exact scaling), without a division per use
   const bool tpow2 = (T & (T - 1)) == 0;
   const double rT = R / dT;
   auto frac_of_range = [&](int tm) -> double { return tpow2 ? (double)tm * rT : (double)tm * R / dT; };
-  // The closed form only ranks: a lane remembers its smallest value and which (s, zero-point)
-  // gave it; the tie key of the enumeration is formed once, for that candidate, afterwards.
-  int best_s = 0, best_zi = 0;
   const int rounds = (2 * t + NTA) / NTA;
   for (int rd = 0; rd < rounds; ++rd) {
     const int s = tid + rd * NTA;
@@ -802,36 +832,35 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
     const int tb = (s < t) ? s : t;            // largest t_min
     const double lo_a = lo0 + frac_of_range(ta);
     const double hi_a = hi0 - frac_of_range(s - ta);
-    const double S = (hi_a - lo_a) / qmax;
+    const double S = div_by_levels(hi_a - lo_a);
     const bool ok = live && (S > 0.0);
     const double Sx = ok ? S : 1.0;
     const double lo_b = lo0 + frac_of_range(tb);
-    const double zf = -rint(lo_a / Sx);
-    const double zl = -rint(lo_b / Sx);
+    const double rS = recip_f64(Sx);
+    const double zf = -rint_quotient(lo_a, Sx, rS);
+    const double zl = -rint_quotient(lo_b, Sx, rS);
     double span = zf - zl;
     if (!(span >= 0.0)) span = 0.0;
     const int nz = ok ? (int)fmin(span, 1.0e6) + 1 : 0;
-    int nzw = nz;
+    // widest lane of the wavefront, rounded up to the width of the walk that will serve it
+    // (votes over the wavefront; the exact maximum only when some lane needs more than one walk)
+    int nzw;
+    if (__ballot(nz > 3) == 0) nzw = __ballot(nz > 2) ? 3 : (__ballot(nz > 0) ? 2 : 0);
+    else if (__ballot(nz > 8) == 0) nzw = __ballot(nz > 6) ? 8 : (__ballot(nz > 4) ? 6 : 4);
+    else {
+      nzw = nz;
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) nzw = max(nzw, __shfl_xor(nzw, o, 64));
+      for (int o = 32; o > 0; o >>= 1) nzw = max(nzw, __shfl_xor(nzw, o, 64));
+    }
+
     for (int z0 = 0; z0 < nzw; z0 += 8) {
-      double loss[8];
       const int cntw = min(8, nzw - z0);
       const double zb = zf - (double)z0;
-      if (cntw <= 2) chunk(std::integral_constant<int, 2>{}, Sx, zb, loss);
-      else if (cntw <= 3) chunk(std::integral_constant<int, 3>{}, Sx, zb, loss);
-      else if (cntw <= 4) chunk(std::integral_constant<int, 4>{}, Sx, zb, loss);
-      else if (cntw <= 6) chunk(std::integral_constant<int, 6>{}, Sx, zb, loss);
-      else chunk(std::integral_constant<int, 8>{}, Sx, zb, loss);
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const int zi = z0 + k;
-        const bool take = (k < cntw) & (zi < nz) & (loss[k] < best.loss);
-        best.loss = take ? loss[k] : best.loss;
-        best.S = take ? S : best.S;
-        best_s = take ? s : best_s;
-        best_zi = take ? zi : best_zi;
-      }
+      if (cntw <= 2) chunk(std::integral_constant<int, 2>{}, Sx, zb, s, z0, nz);
+      else if (cntw <= 3) chunk(std::integral_constant<int, 3>{}, Sx, zb, s, z0, nz);
+      else if (cntw <= 4) chunk(std::integral_constant<int, 4>{}, Sx, zb, s, z0, nz);
+      else if (cntw <= 6) chunk(std::integral_constant<int, 6>{}, Sx, zb, s, z0, nz);
+      else chunk(std::integral_constant<int, 8>{}, Sx, zb, s, z0, nz);
     }
   }
   if (best.loss < INFINITY) {
