@@ -580,8 +580,8 @@ __device__ __forceinline__ void cvt_up(float (&o)[N], const double (&a)[N]) {
 // The closed form cancels (its terms are of the size of sum(omega x^2), the loss is not), so
 // it ranks the candidates to about 1e-10 relative and is not used for the decision itself:
 // every lane's best candidate that lies within 1e-7 of the smallest value found is scored
-// again by the plain evaluation in the original order, and those plain losses decide, with
-// the same tie key as the enumeration.
+// again by the plain evaluation of Eq. 7 over the group's weights (no prefix sums), and those
+// plain losses decide, with the same tie key as the enumeration.
 template <int NTA, int BITS>
 __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restrict__ W, int64_t c,
                                                             int64_t ldw, int g, int n2, int nbk,
@@ -743,8 +743,9 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
       // thresholds (j + 1/2) S as the smallest floats not below them: w < threshold exactly when
       // w < that float
       double td[NB];
+      const double jh = jmin + 0.5;               // (integers far below 2^51 and a half: every sum is exact)
 #pragma unroll
-      for (int i = 0; i < NB; ++i) td[i] = (jmin + (double)i + 0.5) * S;
+      for (int i = 0; i < NB; ++i) td[i] = (jh + (double)i) * S;
       cvt_up<NB>(thr, td);
     }
 #pragma unroll
@@ -889,19 +890,29 @@ __global__ __launch_bounds__(NTA) void affine_sorted_kernel(const float* __restr
   }
   const double lmin = sBestLoss[0];
   __syncthreads();
+  // A wavefront scores its candidates one after the other, all lanes on one candidate: lane l
+  // adds the weights l, l + 64, ... in that order and the 64 partial sums are added pairwise
+  // (lanes 32 apart first), a fixed order.
   double exact = INFINITY;
-  if (best.loss <= lmin + (1.0e-7 * fabs(lmin) + 1.0e-12 * Ctot)) {
-    const double S = best.S, Z = best.Z;
-    const double invS = 1.0 / S;
-    const double cl = -Z, ch = qmax - Z;
-    double loss = 0.0;
-    for (int i = 0; i < g; ++i) {
-      const double w = (double)sW[i];
-      const double u = fmin(fmax(rint(w * invS), cl), ch);
-      const double dlt = fma(u, S, -w);
-      loss = fma(sOm[i] * dlt, dlt, loss);
+  {
+    unsigned long long todo = __ballot(best.loss <= lmin + (1.0e-7 * fabs(lmin) + 1.0e-12 * Ctot));
+    while (todo) {
+      const int src = __ffsll((long long)todo) - 1;
+      todo &= todo - 1;
+      const double S = __shfl(best.S, src, 64), Z = __shfl(best.Z, src, 64);
+      const double invS = 1.0 / S;
+      const double cl = -Z, ch = qmax - Z;
+      double loss = 0.0;
+      for (int i = lane; i < g; i += 64) {
+        const double w = (double)sW[i];
+        const double u = fmin(fmax(rint(w * invS), cl), ch);
+        const double dlt = fma(u, S, -w);
+        loss = fma(sOm[i] * dlt, dlt, loss);
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) loss += __shfl_xor(loss, o, 64);
+      if (lane == src) exact = loss;
     }
-    exact = loss;
   }
   sBestLoss[tid] = exact; sBestKey[tid] = best.key; sBestS[tid] = best.S; sBestZ[tid] = best.Z;
   __syncthreads();
