@@ -322,7 +322,9 @@ __device__ __forceinline__ void tn_fast_loop(TnFastSrc<KT>& sp, TnFastSrc<KT>& s
   }
 }
 
-template <int KT, bool VEC>
+// HALF: -1 = the whole 128 x 128 tile; 0 / 1 = only its upper / lower 64 rows (the sub-tiles
+// tm = HALF of every wavefront), for launches that split a tile between two workgroups.
+template <int KT, bool VEC, int HALF = -1>
 __device__ __forceinline__ void tn_mainloop_fast(const TnGemmArgs& a, float* smem, int64_t kbeg,
                                                  int64_t kend, int64_t m0, int64_t n0, bool diag,
                                                  int wm, int wn, int lane, int tid, Acc2x2& acc) {
@@ -353,7 +355,11 @@ __device__ __forceinline__ void tn_mainloop_fast(const TnGemmArgs& a, float* sme
   // the 4 x 4 sub-tiles (wm + 2 tm, wn + 2 tn) the six with a row index above the column index
   // are left at zero (the reduce kernel mirrors their transposes): wavefront (1, 0) keeps
   // sub-tile (1, 2) alone, the other three drop (wm + 2, wn).
-  if (diag) {
+  if constexpr (HALF == 0) {
+    tn_fast_loop<KT, false, 3>(sp, sq, nst, b0, b1, rp, rq, o, acc);
+  } else if constexpr (HALF == 1) {
+    tn_fast_loop<KT, false, 12>(sp, sq, nst, b0, b1, rp, rq, o, acc);
+  } else if (diag) {
     if (wm * 2 + wn == 2) tn_fast_loop<KT, true, 2>(sp, sq, nst, b0, b1, rp, rq, o, acc);
     else tn_fast_loop<KT, true, 11>(sp, sq, nst, b0, b1, rp, rq, o, acc);
   } else {
@@ -361,15 +367,22 @@ __device__ __forceinline__ void tn_mainloop_fast(const TnGemmArgs& a, float* sme
   }
 }
 
-template <int KT, bool SYM, bool PARTIAL, bool VEC, int MINW = 2>
+// SPLIT_TILE (general product, direct update only): the grid has two workgroups per tile and
+// each computes and updates 64 of the tile's 128 rows.  Both load the whole operand stages (the
+// panels come from L2), so this is for launches whose tiles would otherwise leave compute units
+// idle or unevenly loaded: 2 n half-workgroups spread better over the chip than n whole ones.
+template <int KT, bool SYM, bool PARTIAL, bool VEC, int MINW = 2, bool SPLIT_TILE = false>
 __global__ __launch_bounds__(WG_THREADS, MINW) void tn_gemm_kernel(TnGemmArgs a) {
+  static_assert(!SPLIT_TILE || (!SYM && !PARTIAL), "tiles are split for the direct general update only");
   extern __shared__ __align__(16) float smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: lives in a scalar register
   const int wm = wave >> 1, wn = wave & 1;
 
-  const int work = xcd_swizzle(blockIdx.x, a.splits * a.ntiles);
+  int work = xcd_swizzle(blockIdx.x, a.splits * a.ntiles * (SPLIT_TILE ? 2 : 1));
+  int half = 0;
+  if (SPLIT_TILE) { half = work & 1; work >>= 1; }
   int split, tile, bi, bj;
   if (SYM) {
     // Diagonal tiles do less work (see tn_mainloop_fast) and finish earlier.  Workgroups that
@@ -404,8 +417,66 @@ __global__ __launch_bounds__(WG_THREADS, MINW) void tn_gemm_kernel(TnGemmArgs a)
     // predicate-free loads; the two loops are separate so that each has one load variant
     const bool fast = VEC && (m0 + TILE <= a.M) && (n0 + TILE <= a.N) && ((kend - kbeg) % KT == 0) &&
                       a.ldp < (1 << 24) && a.ldq < (1 << 24);   // 32-bit byte offsets inside a stage
-    if (fast) tn_mainloop_fast<KT, VEC>(a, smem, kbeg, kend, m0, n0, diag, wm, wn, lane, tid, acc);
-    else tn_mainloop_safe<KT, VEC>(a, smem, kbeg, kend, m0, n0, diag, wm, wn, lane, tid, acc);
+    if constexpr (SPLIT_TILE) {
+      // (the guarded loop computes the whole tile; the half that is not this workgroup's is dropped)
+      if (!fast) tn_mainloop_safe<KT, VEC>(a, smem, kbeg, kend, m0, n0, diag, wm, wn, lane, tid, acc);
+      else if (half == 0) tn_mainloop_fast<KT, VEC, 0>(a, smem, kbeg, kend, m0, n0, diag, wm, wn, lane, tid, acc);
+      else tn_mainloop_fast<KT, VEC, 1>(a, smem, kbeg, kend, m0, n0, diag, wm, wn, lane, tid, acc);
+    } else {
+      if (fast) tn_mainloop_fast<KT, VEC>(a, smem, kbeg, kend, m0, n0, diag, wm, wn, lane, tid, acc);
+      else tn_mainloop_safe<KT, VEC>(a, smem, kbeg, kend, m0, n0, diag, wm, wn, lane, tid, acc);
+    }
+  }
+
+  if constexpr (SPLIT_TILE) {
+    // rows 64 * half .. 64 * half + 63 of the tile: the sub-tiles tm = half of every wavefront
+    const bool direct = VEC && (m0 + TILE <= a.M) && (n0 + TILE <= a.N) && (a.ldc % 4 == 0) &&
+                        ((reinterpret_cast<uintptr_t>(a.C) & 15) == 0) && (n0 % 4 == 0);
+    if (direct) {
+      float* cbase = a.C + (m0 + 64 * half) * a.ldc + n0;
+      float4 cv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int f = tid + u * WG_THREADS;
+        cv[u] = *reinterpret_cast<const float4*>(cbase + (int64_t)(f >> 5) * a.ldc + 4 * (f & 31));
+      }
+      __syncthreads();                             // the operand buffers are no longer read
+#pragma unroll
+      for (int tm = 0; tm < 2; ++tm) {
+        if (tm != half) continue;
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            smem[(acc_row(wm, tm, v, lane) - 64 * tm) * TILE + acc_col(wn, tn, lane)] = a.alpha * acc.t[tm][tn][v];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int f = tid + u * WG_THREADS;
+        const float4 d = *reinterpret_cast<const float4*>(smem + (f >> 5) * TILE + 4 * (f & 31));
+        cv[u].x += d.x; cv[u].y += d.y; cv[u].z += d.z; cv[u].w += d.w;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int f = tid + u * WG_THREADS;
+        *reinterpret_cast<float4*>(cbase + (int64_t)(f >> 5) * a.ldc + 4 * (f & 31)) = cv[u];
+      }
+    } else {
+#pragma unroll
+      for (int tm = 0; tm < 2; ++tm) {
+        if (tm != half) continue;
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int64_t row = m0 + acc_row(wm, tm, v, lane);
+            const int64_t col = n0 + acc_col(wn, tn, lane);
+            if (row < a.M && col < a.N) a.C[row * a.ldc + col] += a.alpha * acc.t[tm][tn][v];
+          }
+      }
+    }
+    return;
   }
 
   if (PARTIAL) {

@@ -111,6 +111,8 @@ extern "C" lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t l
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds));
     LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, false, false, false, MINW>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds));
+    LQ_CHECK_HIP(hipFuncSetAttribute((const void*)lq::tn_gemm_kernel<KT, false, false, true, MINW, true>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds));
     once.done();
   }
 
@@ -142,6 +144,18 @@ extern "C" lq_status lq_quantize_layer(float* W, int64_t r, int64_t c, int64_t l
       if (vec) hipLaunchKernelGGL(lq::tn_small_kernel<true>, grid3, block2, 0, st, t);
       else hipLaunchKernelGGL(lq::tn_small_kernel<false>, grid3, block2, 0, st, t);
       LQ_CHECK_LAUNCH("tn_small_kernel(trailing)");
+      return LQ_OK;
+    }
+    // Few tiles (layers with few rows, the last groups of any layer): a compute unit's share of
+    // the launch is ceil(tiles / 256) whole tiles, or ceil(2 tiles / 256) halves if every tile is
+    // split between two workgroups.  The halves are taken where that share is smaller, and
+    // wherever not every compute unit gets a whole tile.
+    constexpr int64_t CUS = 256;
+    const int64_t whole = lq::ceil_div((int64_t)t.ntiles, CUS) * 2, halves = lq::ceil_div(2 * (int64_t)t.ntiles, CUS);
+    if (vec && t.ntiles <= 8 * CUS && (halves < whole || t.ntiles <= CUS)) {
+      hipLaunchKernelGGL((lq::tn_gemm_kernel<KT, false, false, true, MINW, true>), dim3((unsigned)(2 * t.ntiles)),
+                         block2, gemm_lds, st, t);
+      LQ_CHECK_LAUNCH("tn_gemm_kernel(trailing, split tiles)");
       return LQ_OK;
     }
     dim3 grid2((unsigned)t.ntiles);
