@@ -200,7 +200,9 @@ def test_fit_grid_affine(r, c, group, bits, T):
         orf = orc.eq7_objective(W[k, sl], om[sl], ref[k, gi, 0], ref[k, gi, 1], bits)
         worst = max(worst, og / orf - 1.0)
     _say(f"  groups matching {ok.mean():.4f}; worst objective excess of the rest {worst:.2e}")
-    assert ok.mean() >= 0.97
+    # groups that differ must be ties of Eq. 7 (asserted below); they are rare, but on fewer than
+    # 34 groups a single one is already more than 3 %
+    assert ok.mean() >= 0.97 or (~ok).sum() <= 1
     assert worst <= 1e-5
 
 
